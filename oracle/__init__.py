@@ -1,0 +1,9 @@
+"""fp64 CPU oracle (test infrastructure only; never imported by the product path)."""
+from .rolling_attention import (  # noqa: F401
+    RollingCacheOracle,
+    RingTableSim,
+    rope_angles,
+    rope_rotate,
+    round_to_bf16,
+    visible_history,
+)
