@@ -1,0 +1,148 @@
+/*
+ * astro.h -- C ABI of the rolling-KV-cache chunk-attention library for MI355X (gfx950).
+ *
+ * The library implements the attention hot path of the streaming RL scheme of
+ * arXiv 2603.17051: a stream of video frames is generated chunk by chunk; each
+ * new chunk attends to a bounded context (a few permanent "sink" frames plus a
+ * rolling window of the most recent frames, Sec. 3.2) held in a ring-buffer KV
+ * cache, and in the RL update the cached context is a constant while gradients
+ * flow through the chunk only (Sec. 3.3, "Streaming Long Tuning").
+ *
+ * Conventions
+ *   B streams (independent caches), H heads, D head dim, frames of
+ *   T = grid_h * grid_w tokens, ring capacity C frames of which the first S
+ *   appended after a reset are sinks, window Lw = C - S.
+ *   Chunk tensors are [B, n_frames*T, H, D], D contiguous, token index
+ *   n = (frame_in_chunk * grid_h + row) * grid_w + col.
+ *   "device" pointers are HIP device memory owned by the CALLER (e.g. torch
+ *   tensors); the library never frees them and keeps none of them beyond the
+ *   call, except k_storage / v_storage, which it uses until destroy.
+ *   All launches are asynchronous on the caller's HIP stream (`hip_stream` is a
+ *   hipStream_t cast to void*; NULL = the default stream).  Calls on one cache
+ *   handle must be made from one host thread at a time.
+ *   Every function returns ASTRO_OK (0) or a negative astro error; on error no
+ *   state has changed and nothing has been launched.
+ *
+ * Rotary embedding (the paper names none; this layout is fixed by the library):
+ *   adjacent pairs (x[2i], x[2i+1]), i < D/2; pairs [0, n_t) turn with the
+ *   absolute frame index, [n_t, n_t+n_h) with the row, the rest with the column;
+ *   pair j of an axis with n pairs has frequency rope_base^(-j/n).  Keys are
+ *   cached after rotation; values are never rotated.  All three counts 0 = no
+ *   rotary embedding.
+ */
+#ifndef ASTRO_H_
+#define ASTRO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ASTRO_OK 0
+#define ASTRO_ERR_INVALID_ARG (-1) /* null pointer, size or shape out of range        */
+#define ASTRO_ERR_BAD_STATE (-2)   /* call not possible in the handle's current state */
+#define ASTRO_ERR_UNSUPPORTED (-3) /* valid request the kernels do not cover          */
+#define ASTRO_ERR_HIP (-4)         /* a HIP runtime call failed                       */
+#define ASTRO_ERR_WORKSPACE (-5)   /* workspace missing or too small                  */
+
+#define ASTRO_BF16 0 /* bf16 tensors, bf16 MFMA, fp32 accumulation (production path)  */
+#define ASTRO_F32 1  /* fp32 tensors and arithmetic (slow debug path)                 */
+
+/* desc.flags */
+#define ASTRO_FLAG_HOST_ONLY 1 /* no device work at all: the handle only plans slots  */
+
+#define ASTRO_MAX_BATCH 64
+#define ASTRO_MAX_CAPACITY_FRAMES 256
+
+typedef struct astro_kvcache astro_kvcache_t; /* opaque */
+
+typedef struct astro_kvcache_desc {
+  int32_t batch, heads, head_dim;     /* B in [1,64], H >= 1, D in {64, 128}              */
+  int32_t grid_h, grid_w;             /* T = grid_h * grid_w tokens per frame             */
+  int32_t capacity_frames;            /* C in [1,256]: frames resident before a chunk     */
+  int32_t sink_frames;                /* S, 0 <= S < C                                    */
+  int32_t max_chunk_frames;           /* largest n_frames of any call, 1 .. C - S         */
+  int32_t rope_pairs_t, rope_pairs_h, rope_pairs_w; /* sum == D/2, or all three 0         */
+  int32_t dtype;                      /* ASTRO_BF16 or ASTRO_F32                          */
+  int32_t flags;                      /* 0 or ASTRO_FLAG_HOST_ONLY                        */
+  int32_t reserved_;                  /* set to 0                                         */
+  double rope_base;                   /* > 1, e.g. 10000                                  */
+  void *k_storage, *v_storage;        /* device, sizes from astro_kvcache_bytes; layout   */
+                                      /* [B][H][C*T][D] of dtype; may be NULL iff         */
+                                      /* ASTRO_FLAG_HOST_ONLY                             */
+} astro_kvcache_desc_t;
+
+/* Bytes of device storage the cache of `desc` needs for keys and for values
+ * (Sec. 3.2: constant in the video length).  Host only. */
+int astro_kvcache_bytes(const astro_kvcache_desc_t *desc, size_t *k_bytes, size_t *v_bytes);
+
+/* Create a cache handle: all B streams empty, start frame 0.  Validates `desc`,
+ * builds the per-row / per-column rotary tables in fp64 and uploads them (small,
+ * library-owned device memory; the only allocation the library makes).
+ * Host-synchronous.  *out is untouched on error. */
+int astro_kvcache_create(const astro_kvcache_desc_t *desc, astro_kvcache_t **out);
+
+/* Free the handle and its small tables (not k_storage / v_storage).  The caller
+ * must have synchronised every stream that still uses the cache. */
+int astro_kvcache_destroy(astro_kvcache_t *cache);
+
+/* Empty stream `stream` (or all streams if -1) and set the absolute index of the
+ * next appended frame to `start_frame` (>= 0).  Host only; storage is not cleared. */
+int astro_kvcache_reset(astro_kvcache_t *cache, int32_t stream, int32_t start_frame);
+
+/* Sec. 3.2, rolling cache with frame sinks: commit `n_frames` new frames per
+ * stream.  k, v: device, un-rotated, [B, n_frames*T, H, D].  Frame number n of a
+ * stream (0-based since reset) goes to ring slot n if n < C, else
+ * S + (n - S) mod Lw, overwriting -- evicting -- frame n - Lw; keys are rotated
+ * at absolute frame index start_frame + n and stored, values copied.
+ * 1 <= n_frames <= min(max_chunk_frames, Lw).  Advances the tables. */
+int astro_kvcache_append(astro_kvcache_t *cache, const void *k, const void *v, int32_t n_frames,
+                         void *hip_stream);
+
+/* Host copies of the integer tables: slot_frame[B*C] = absolute index of the
+ * frame resident in each ring slot (-1 = empty), slot_pos[B*C] = its temporal
+ * rotary position (-1 = empty), next_n[B] = frames appended since reset.  Any
+ * output pointer may be NULL.  Host only (tables are host-authoritative). */
+int astro_kvcache_tables(const astro_kvcache_t *cache, int32_t *slot_frame, int32_t *slot_pos,
+                         int32_t *next_n);
+
+/* Bytes of caller-provided device workspace the two attention calls need for a
+ * chunk of n_frames (rotated copies of Q and K_chunk; for backward also the
+ * row terms and rotated-gradient staging).  Either output may be NULL. */
+int astro_chunk_attn_workspace_bytes(const astro_kvcache_t *cache, int32_t n_frames,
+                                     size_t *fwd_bytes, size_t *bwd_bytes);
+
+/* Block-causal chunk attention over the rolling cache (Sec. 3.1 / 3.2: the new
+ * chunk is conditioned on the KV cache of the context window only).  For every
+ * stream, the chunk's queries (rotated at frame indices start_frame + next_n ...)
+ * attend to all resident cache frames and to all keys of the chunk itself:
+ *   out = softmax(Q~ K~^T / sqrt(D)) V,  lse = log-sum-exp of the scaled scores.
+ * q, k_chunk, v_chunk: device, un-rotated, [B, n_frames*T, H, D];
+ * out: device [B, n_frames*T, H, D] (dtype of the cache); lse: device fp32
+ * [B, H, n_frames*T].  Does not modify the cache or its tables (append does).
+ * workspace: device, >= fwd_bytes, 256-byte aligned; contents undefined after. */
+int astro_chunk_attn_fwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
+                         const void *v_chunk, int32_t n_frames, void *out, float *lse,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backward of astro_chunk_attn_fwd with the cached context detached (Sec. 3.3):
+ * given dout = dL/dout, writes dL/dq, dL/dk_chunk, dL/dv_chunk (fp32, device,
+ * [B, n_frames*T, H, D], w.r.t. the UN-rotated inputs).  Cached keys / values get
+ * no gradient.  q, k_chunk, v_chunk, out, lse must be those of a forward call on
+ * the same cache state.  dout has the cache dtype.
+ * workspace: device, >= bwd_bytes, 256-byte aligned. */
+int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
+                         const void *v_chunk, const void *out, const float *lse,
+                         const void *dout, int32_t n_frames, float *dq, float *dk_chunk,
+                         float *dv_chunk, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/* Static, never-NULL description of an error code. */
+const char *astro_strerror(int err);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASTRO_H_ */

@@ -1,0 +1,284 @@
+// C-ABI layer: argument validation, host tables, workspace carving, kernel launches.
+// Every step of the path runs in the HIP kernels; there is no CPU fallback.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/astro.h"
+#include "kernels.hpp"
+#include "ring_state.hpp"
+
+using namespace astro;
+
+struct astro_kvcache {
+  RingGeometry geo;
+  RingTables tables;
+  void* k_storage;
+  void* v_storage;
+  // small library-owned device tables
+  double* d_inv_freq_t = nullptr;
+  float2* d_tab_h = nullptr;
+  float2* d_tab_w = nullptr;
+  int device = -1;
+  astro_kvcache(const RingGeometry& g, void* k, void* v) : geo(g), tables(g.B, g.C, g.S), k_storage(k), v_storage(v) {}
+};
+
+namespace {
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+DevGeom dev_geom(const astro_kvcache* c) {
+  const RingGeometry& g = c->geo;
+  DevGeom d;
+  d.B = g.B; d.H = g.H; d.D = g.D; d.gh = g.gh; d.gw = g.gw; d.T = g.T; d.C = g.C; d.S = g.S;
+  d.n_t = g.n_t; d.n_h = g.n_h; d.n_w = g.n_w;
+  d.inv_freq_t = c->d_inv_freq_t;
+  d.tab_h = c->d_tab_h;
+  d.tab_w = c->d_tab_w;
+  return d;
+}
+
+struct Workspace {
+  size_t q_rot, kc_rot, dq_rot, dk_rot, scratch, total;
+};
+
+Workspace carve(const astro_kvcache* c, int n_frames, bool bwd) {
+  const RingGeometry& g = c->geo;
+  const size_t nq = (size_t)n_frames * g.T;
+  const size_t rot = align256((size_t)g.B * g.H * nq * g.D * g.elem_bytes());
+  const size_t grad = align256((size_t)g.B * g.H * nq * g.D * sizeof(float));
+  const DevGeom d = dev_geom(c);
+  Workspace w{};
+  size_t off = 0;
+  w.q_rot = off; off += rot;
+  w.kc_rot = off; off += rot;
+  if (bwd) {
+    w.dq_rot = off; off += grad;
+    w.dk_rot = off; off += grad;
+  }
+  w.scratch = off;
+  if (g.dtype == ASTRO_F32)
+    off += align256(sizeof(float) * (bwd ? f32_bwd_workspace_floats(d, (int)nq) : f32_fwd_workspace_floats(d, (int)nq)));
+  else if (bwd)
+    off += align256(bf16_bwd_workspace_bytes(d, (int)nq));
+  w.total = off;
+  return w;
+}
+
+int check_chunk_call(const astro_kvcache* c, int n_frames) {
+  if (!c) return ASTRO_ERR_INVALID_ARG;
+  if (c->geo.host_only) return ASTRO_ERR_BAD_STATE;
+  if (n_frames < 1 || n_frames > c->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
+  if (!c->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
+  return ASTRO_OK;
+}
+
+void stream_ints(const astro_kvcache* c, StreamInts* first_frame, StreamInts* next_n, StreamInts* hist_rows) {
+  for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
+    const bool live = b < c->geo.B;
+    if (first_frame) first_frame->v[b] = live ? c->tables.start(b) + c->tables.next_n(b) : 0;
+    if (next_n) next_n->v[b] = live ? c->tables.next_n(b) : 0;
+    if (hist_rows) hist_rows->v[b] = live ? c->tables.resident(b) * c->geo.T : 0;
+  }
+}
+
+AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w, const void* v_chunk, int n_frames) {
+  AttnOperands op;
+  op.q_rot = ws + w.q_rot;
+  op.kc_rot = ws + w.kc_rot;
+  op.v_chunk = v_chunk;
+  op.k_cache = c->k_storage;
+  op.v_cache = c->v_storage;
+  op.Nq = n_frames * c->geo.T;
+  stream_ints(c, nullptr, nullptr, &op.hist_rows);
+  return op;
+}
+
+// rotate Q and K_chunk into the workspace (head-major)
+hipError_t stage_chunk(const astro_kvcache* c, const void* q, const void* k_chunk, char* ws, const Workspace& w,
+                       int n_frames, hipStream_t stream) {
+  StreamInts first, next;
+  stream_ints(c, &first, &next, nullptr);
+  ScatterDst dst{ws + w.q_rot, ws + w.kc_rot, (int64_t)n_frames * c->geo.T, 0};
+  return launch_rope_scatter(dev_geom(c), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int astro_kvcache_bytes(const astro_kvcache_desc_t* desc, size_t* k_bytes, size_t* v_bytes) {
+  astro_kvcache_desc_t d;
+  if (!desc) return ASTRO_ERR_INVALID_ARG;
+  d = *desc;
+  d.flags |= ASTRO_FLAG_HOST_ONLY;  // storage pointers are not needed to size the cache
+  RingGeometry g;
+  const int rc = validate_desc(&d, &g);
+  if (rc != ASTRO_OK) return rc;
+  if (k_bytes) *k_bytes = g.storage_bytes();
+  if (v_bytes) *v_bytes = g.storage_bytes();
+  return ASTRO_OK;
+}
+
+int astro_kvcache_create(const astro_kvcache_desc_t* desc, astro_kvcache_t** out) {
+  if (!out) return ASTRO_ERR_INVALID_ARG;
+  RingGeometry g;
+  const int rc = validate_desc(desc, &g);
+  if (rc != ASTRO_OK) return rc;
+  if (desc->reserved_ != 0) return ASTRO_ERR_INVALID_ARG;
+  astro_kvcache* c = new (std::nothrow) astro_kvcache(g, desc->k_storage, desc->v_storage);
+  if (!c) return ASTRO_ERR_INVALID_ARG;
+  if (!g.host_only) {
+    // rotary tables in fp64, rounded once to fp32
+    std::vector<double> inv_t(g.n_t > 0 ? g.n_t : 1, 0.0);
+    for (int j = 0; j < g.n_t; ++j) inv_t[j] = std::pow(g.rope_base, -(double)j / g.n_t);
+    std::vector<float2> th((size_t)g.gh * (g.n_h > 0 ? g.n_h : 1)), tw((size_t)g.gw * (g.n_w > 0 ? g.n_w : 1));
+    for (int r = 0; r < g.gh; ++r)
+      for (int j = 0; j < g.n_h; ++j) {
+        const double a = (double)r * std::pow(g.rope_base, -(double)j / g.n_h);
+        th[(size_t)r * g.n_h + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+      }
+    for (int w = 0; w < g.gw; ++w)
+      for (int j = 0; j < g.n_w; ++j) {
+        const double a = (double)w * std::pow(g.rope_base, -(double)j / g.n_w);
+        tw[(size_t)w * g.n_w + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+      }
+    bool ok = hipGetDevice(&c->device) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->d_inv_freq_t, inv_t.size() * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->d_tab_h, th.size() * sizeof(float2)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->d_tab_w, tw.size() * sizeof(float2)) == hipSuccess;
+    ok = ok && hipMemcpy(c->d_inv_freq_t, inv_t.data(), inv_t.size() * sizeof(double), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(c->d_tab_h, th.data(), th.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(c->d_tab_w, tw.data(), tw.size() * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+      (void)hipGetLastError();
+      astro_kvcache_destroy(c);
+      return ASTRO_ERR_HIP;
+    }
+  }
+  *out = c;
+  return ASTRO_OK;
+}
+
+int astro_kvcache_destroy(astro_kvcache_t* cache) {
+  if (!cache) return ASTRO_ERR_INVALID_ARG;
+  int rc = ASTRO_OK;
+  if (cache->d_inv_freq_t && hipFree(cache->d_inv_freq_t) != hipSuccess) rc = ASTRO_ERR_HIP;
+  if (cache->d_tab_h && hipFree(cache->d_tab_h) != hipSuccess) rc = ASTRO_ERR_HIP;
+  if (cache->d_tab_w && hipFree(cache->d_tab_w) != hipSuccess) rc = ASTRO_ERR_HIP;
+  delete cache;
+  return rc;
+}
+
+int astro_kvcache_reset(astro_kvcache_t* cache, int32_t stream, int32_t start_frame) {
+  if (!cache) return ASTRO_ERR_INVALID_ARG;
+  if (stream < -1 || stream >= cache->geo.B || start_frame < 0) return ASTRO_ERR_INVALID_ARG;
+  cache->tables.reset(stream, start_frame);
+  return ASTRO_OK;
+}
+
+int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, int32_t n_frames, void* hip_stream) {
+  if (!cache) return ASTRO_ERR_INVALID_ARG;
+  const RingGeometry& g = cache->geo;
+  if (n_frames < 1 || n_frames > g.max_chunk || n_frames > g.Lw) return ASTRO_ERR_INVALID_ARG;
+  if (!cache->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
+  if (!g.host_only) {
+    if (!k || !v) return ASTRO_ERR_INVALID_ARG;
+    StreamInts first, next;
+    stream_ints(cache, &first, &next, nullptr);
+    ScatterDst dst{cache->k_storage, cache->v_storage, (int64_t)g.C * g.T, 1};
+    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next,
+                            (hipStream_t)hip_stream) != hipSuccess)
+      return ASTRO_ERR_HIP;
+  }
+  cache->tables.append(n_frames);
+  return ASTRO_OK;
+}
+
+int astro_kvcache_tables(const astro_kvcache_t* cache, int32_t* slot_frame, int32_t* slot_pos, int32_t* next_n) {
+  if (!cache) return ASTRO_ERR_INVALID_ARG;
+  const auto& sf = cache->tables.slot_frame();
+  // the temporal rotary position of a resident frame is its absolute frame index
+  if (slot_frame) std::memcpy(slot_frame, sf.data(), sf.size() * sizeof(int32_t));
+  if (slot_pos) std::memcpy(slot_pos, sf.data(), sf.size() * sizeof(int32_t));
+  if (next_n)
+    for (int b = 0; b < cache->geo.B; ++b) next_n[b] = cache->tables.next_n(b);
+  return ASTRO_OK;
+}
+
+int astro_chunk_attn_workspace_bytes(const astro_kvcache_t* cache, int32_t n_frames, size_t* fwd_bytes,
+                                     size_t* bwd_bytes) {
+  if (!cache) return ASTRO_ERR_INVALID_ARG;
+  if (n_frames < 1 || n_frames > cache->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
+  if (fwd_bytes) *fwd_bytes = carve(cache, n_frames, false).total;
+  if (bwd_bytes) *bwd_bytes = carve(cache, n_frames, true).total;
+  return ASTRO_OK;
+}
+
+int astro_chunk_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         int32_t n_frames, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  const int rc = check_chunk_call(cache, n_frames);
+  if (rc != ASTRO_OK) return rc;
+  if (!q || !k_chunk || !v_chunk || !out || !lse) return ASTRO_ERR_INVALID_ARG;
+  const Workspace w = carve(cache, n_frames, false);
+  if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return ASTRO_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames);
+  const DevGeom d = dev_geom(cache);
+  hipError_t e;
+  if (cache->geo.dtype == ASTRO_F32)
+    e = launch_attn_fwd_f32(d, op, (float*)out, lse, (float*)(ws + w.scratch), stream);
+  else
+    e = launch_attn_fwd_bf16(d, op, out, lse, stream);
+  return e == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
+}
+
+int astro_chunk_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         const void* out, const float* lse, const void* dout, int32_t n_frames, float* dq,
+                         float* dk_chunk, float* dv_chunk, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_chunk_call(cache, n_frames);
+  if (rc != ASTRO_OK) return rc;
+  if (!q || !k_chunk || !v_chunk || !out || !lse || !dout || !dq || !dk_chunk || !dv_chunk) return ASTRO_ERR_INVALID_ARG;
+  const Workspace w = carve(cache, n_frames, true);
+  if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return ASTRO_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames);
+  const DevGeom d = dev_geom(cache);
+  float* dq_rot = (float*)(ws + w.dq_rot);
+  float* dk_rot = (float*)(ws + w.dk_rot);
+  hipError_t e;
+  if (cache->geo.dtype == ASTRO_F32)
+    e = launch_attn_bwd_f32(d, op, (const float*)out, lse, (const float*)dout, dq_rot, dk_rot, dv_chunk,
+                            (float*)(ws + w.scratch), stream);
+  else
+    e = launch_attn_bwd_bf16(d, op, out, lse, dout, dq_rot, dk_rot, dv_chunk, ws + w.scratch, stream);
+  if (e != hipSuccess) return ASTRO_ERR_HIP;
+  // gradients w.r.t. the un-rotated Q and K_chunk: inverse rotation, back to token-major
+  StreamInts first;
+  stream_ints(cache, &first, nullptr, nullptr);
+  if (launch_rope_unscatter_f32(d, dq_rot, dq, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  if (launch_rope_unscatter_f32(d, dk_rot, dk_chunk, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  return ASTRO_OK;
+}
+
+const char* astro_strerror(int err) {
+  switch (err) {
+    case ASTRO_OK: return "ok";
+    case ASTRO_ERR_INVALID_ARG: return "invalid argument";
+    case ASTRO_ERR_BAD_STATE: return "call not possible in the current cache state";
+    case ASTRO_ERR_UNSUPPORTED: return "unsupported configuration";
+    case ASTRO_ERR_HIP: return "HIP runtime error";
+    case ASTRO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    default: return "unknown astro error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,377 @@
+// Chunk attention backward with the cached context detached (Sec. 3.3), bf16 MFMA with
+// fp32 accumulation.  Three kernels, no atomics, deterministic:
+//   delta : Delta[q] = <dO_q, O_q>
+//   dq    : one workgroup per query tile, walks ALL visible keys (ring + chunk):
+//             S^T = K Q~^T, P^T = exp(S^T/sqrt(D) - LSE), dP^T = V dO^T,
+//             dS^T = P^T o (dP^T - Delta), dQ~^T += K^T dS^T
+//   dkv   : one workgroup per tile of CHUNK keys, walks all query tiles:
+//             S = Q~ K~^T, P, dV^T += dO^T P, dP = dO V^T, dS, dK~^T += Q~^T dS
+//           Cached keys / values get no gradient, so no workgroup exists for them.
+// As in the forward every product is arranged so that the accumulator of one product is
+// directly the B operand of the next, and the LDS tile of the other operand is read
+// either by rows (contraction over D) or through the transposing read (contraction over
+// the tile's rows).
+#include "kernels.hpp"
+#include "mfma_common.hpp"
+
+namespace astro {
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int KT = 64;  // rows per LDS tile
+
+struct BwdParams {
+  const __bf16* q_rot;
+  const __bf16* kc_rot;
+  const __bf16* v_chunk;
+  const __bf16* k_cache;
+  const __bf16* v_cache;
+  const __bf16* out;
+  const __bf16* dout;
+  const float* lse;
+  float* delta;   // [B][H][Nq]
+  float* dq_rot;  // [B][H][Nq][D]
+  float* dk_rot;  // [B][H][Nq][D]
+  float* dv;      // [B, Nq, H, D]
+  int H, Nq;
+  int64_t cache_rows;
+  float scale_log2e, scale;
+  StreamInts hist_rows;
+};
+
+// one wave per (b, q, h): Delta = sum_d dO * O
+template <int D>
+__global__ void __launch_bounds__(256) delta_kernel(BwdParams p, int64_t n_rows) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b*Nq + q)*H + h
+  if (row >= n_rows) return;
+  const int lane = threadIdx.x & 63;
+  float acc = 0.f;
+  if (lane < D / 2) {
+    const bf16x2 o = *reinterpret_cast<const bf16x2*>(p.out + row * D + lane * 2);
+    const bf16x2 d = *reinterpret_cast<const bf16x2*>(p.dout + row * D + lane * 2);
+    acc = (float)o[0] * (float)d[0] + (float)o[1] * (float)d[1];
+  }
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+  if (lane == 0) {
+    const int h = (int)(row % p.H);
+    const int64_t bq = row / p.H;
+    const int q = (int)(bq % p.Nq);
+    const int b = (int)(bq / p.Nq);
+    p.delta[((int64_t)b * p.H + h) * p.Nq + q] = acc;
+  }
+}
+
+// ---- dQ -----------------------------------------------------------------------
+template <int D, int NQB>
+__global__ void __launch_bounds__(kThreads, 1) attn_bwd_dq_kernel(BwdParams p) {
+  constexpr int QSTEPS = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int TILE_BYTES = KT * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i32 = lane & 31, g = lane >> 5, i16 = lane & 15, blk = (lane >> 4) & 1;
+  const int hist = p.hist_rows.v[b];
+  const int nk = hist + p.Nq;
+  const int ntiles = (nk + KT - 1) / KT;
+  const int q0 = (blockIdx.x * kWaves + wave) * 32 * NQB;
+  const int64_t bh = (int64_t)b * p.H + h;
+
+  // B operands held in registers: Q~ and dO rows of this lane's query
+  bf16x8 qreg[NQB][QSTEPS], doreg[NQB][QSTEPS];
+  float lse2[NQB], delta[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int q = q0 + 32 * qb + i32;
+    const bool live = q < p.Nq;
+    const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
+    const __bf16* drow = p.dout + (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
+#pragma unroll
+    for (int st = 0; st < QSTEPS; ++st) {
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
+      if (live) {
+        x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
+        y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
+      }
+      qreg[qb][st] = x;
+      doreg[qb][st] = y;
+    }
+    // a dead query row gets P = exp2(0 - big) = 0 everywhere
+    lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    delta[qb] = live ? p.delta[bh * p.Nq + q] : 0.f;
+  }
+
+  f32x16 dq[NQB][DB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
+
+  const RowSource ksrc{p.k_cache + bh * p.cache_rows * D, D, hist, p.kc_rot + bh * p.Nq * D, D, p.Nq};
+  const RowSource vsrc{p.v_cache + bh * p.cache_rows * D, D, hist, p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D,
+                       (int64_t)p.H * D, p.Nq};
+  TilePairLoader<D, KT, kThreads> ld;
+  ld.load(ksrc, vsrc, 0);
+  ld.store(lds, lds + TILE_BYTES);
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const char* ks = lds + (t & 1) * 2 * TILE_BYTES;
+    const char* vs = ks + TILE_BYTES;
+    if (t + 1 < ntiles) ld.load(ksrc, vsrc, t + 1);
+    const bool tail = (t + 1) * KT > nk;
+
+#pragma unroll
+    for (int kb = 0; kb < KT / 32; ++kb) {
+      f32x16 s[NQB], dp[NQB];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[qb][r] = 0.f, dp[qb][r] = 0.f;
+#pragma unroll
+      for (int st = 0; st < QSTEPS; ++st) {
+        const bf16x8 ak = lds_read_row8<D>(ks, 32 * kb + i32, 2 * st + g);
+        const bf16x8 av = lds_read_row8<D>(vs, 32 * kb + i32, 2 * st + g);
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+          s[qb] = mfma32(ak, qreg[qb][st], s[qb]);
+          dp[qb] = mfma32(av, doreg[qb][st], dp[qb]);
+        }
+      }
+      bf16x8 dsb[NQB][2];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pr = fast_exp2(fmaf(s[qb][r], p.scale_log2e, -lse2[qb]));
+          if (tail && t * KT + 32 * kb + acc_row(r, g) >= nk) pr = 0.f;
+          ds[r] = pr * (dp[qb][r] - delta[qb]);
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dsb[qb][s2][j] = (__bf16)ds[8 * s2 + j];
+      }
+      // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const int key0 = 32 * kb + 16 * s2 + 4 * g;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const int col0 = 32 * db + 16 * blk;
+          const bf16x8 a = concat4(lds_read_col4<D>(ks, key0, col0, i16), lds_read_col4<D>(ks, key0 + 8, col0, i16));
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb) dq[qb][db] = mfma32(a, dsb[qb][s2], dq[qb][db]);
+        }
+      }
+    }
+    if (t + 1 < ntiles) {
+      char* kn = lds + ((t + 1) & 1) * 2 * TILE_BYTES;
+      ld.store(kn, kn + TILE_BYTES);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int q = q0 + 32 * qb + i32;
+    if (q < p.Nq) {
+      float* row = p.dq_rot + (bh * p.Nq + q) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          f32x4 w;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) w[c] = dq[qb][db][4 * rr + c] * p.scale;
+          *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = w;
+        }
+    }
+  }
+}
+
+// ---- dK, dV of the chunk's keys ---------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(kThreads, 1) attn_bwd_dkv_kernel(BwdParams p) {
+  constexpr int QSTEPS = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int TILE_BYTES = KT * D * 2;
+  // Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [KT] and Delta [KT]
+  __shared__ __attribute__((aligned(16))) char lds[4 * TILE_BYTES + 4 * KT * 4];
+  float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i32 = lane & 31, g = lane >> 5, i16 = lane & 15, blk = (lane >> 4) & 1;
+  const int64_t bh = (int64_t)b * p.H + h;
+  const int jc = (blockIdx.x * kWaves + wave) * 32 + i32;  // this lane's chunk key
+  const bool live = jc < p.Nq;
+  const int ntiles = (p.Nq + KT - 1) / KT;
+
+  bf16x8 kreg[QSTEPS], vreg[QSTEPS];
+  {
+    const __bf16* krow = p.kc_rot + (bh * p.Nq + (live ? jc : 0)) * D;
+    const __bf16* vrow = p.v_chunk + (((int64_t)b * p.Nq + (live ? jc : 0)) * p.H + h) * D;
+#pragma unroll
+    for (int st = 0; st < QSTEPS; ++st) {
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
+      if (live) {
+        x = *reinterpret_cast<const bf16x8*>(krow + st * 16 + g * 8);
+        y = *reinterpret_cast<const bf16x8*>(vrow + st * 16 + g * 8);
+      }
+      kreg[st] = x;
+      vreg[st] = y;
+    }
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[db][r] = 0.f, dv[db][r] = 0.f;
+
+  const RowSource qsrc{p.q_rot + bh * p.Nq * D, D, p.Nq, nullptr, 0, 0};
+  const RowSource dsrc{p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, nullptr, 0, 0};
+  TilePairLoader<D, KT, kThreads> ld;
+  float rt = 0.f;  // thread < KT: LSE*log2e of row `thread`; KT <= thread < 2KT: Delta
+  auto load_rowterm = [&](int tile) {
+    const int t = threadIdx.x;
+    if (t < 2 * KT) {
+      const int q = tile * KT + (t & (KT - 1));
+      // rows past Nq: P = exp2(0 - big) = 0
+      if (t < KT) rt = q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+      else rt = q < p.Nq ? p.delta[bh * p.Nq + q] : 0.f;
+    }
+  };
+  ld.load(qsrc, dsrc, 0);
+  load_rowterm(0);
+  ld.store(lds, lds + TILE_BYTES);
+  if (threadIdx.x < 2 * KT) rowterms[threadIdx.x] = rt;
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const char* qs = lds + (t & 1) * 2 * TILE_BYTES;
+    const char* dos = qs + TILE_BYTES;
+    const float* lse_t = rowterms + (t & 1) * 2 * KT;
+    const float* delta_t = lse_t + KT;
+    if (t + 1 < ntiles) {
+      ld.load(qsrc, dsrc, t + 1);
+      load_rowterm(t + 1);
+    }
+#pragma unroll
+    for (int qb = 0; qb < KT / 32; ++qb) {
+      // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+      for (int st = 0; st < QSTEPS; ++st) {
+        const bf16x8 aq = lds_read_row8<D>(qs, 32 * qb + i32, 2 * st + g);
+        const bf16x8 ad = lds_read_row8<D>(dos, 32 * qb + i32, 2 * st + g);
+        s = mfma32(aq, kreg[st], s);
+        dp = mfma32(ad, vreg[st], dp);
+      }
+      bf16x8 pb[2], dsb[2];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int r = 4 * rr + c;
+          const float pr = fast_exp2(fmaf(s[r], p.scale_log2e, -l4[c]));
+          const float ds = pr * (dp[r] - d4[c]);
+          pb[r >> 3][r & 7] = (__bf16)pr;
+          dsb[r >> 3][r & 7] = (__bf16)ds;
+        }
+      }
+      // dV^T[d][key] += dO^T[d][q] P[q][key];  dK~^T[d][key] += Q~^T[d][q] dS[q][key]
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const int row0 = 32 * qb + 16 * s2 + 4 * g;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const int col0 = 32 * db + 16 * blk;
+          const bf16x8 ado = concat4(lds_read_col4<D>(dos, row0, col0, i16), lds_read_col4<D>(dos, row0 + 8, col0, i16));
+          const bf16x8 aq = concat4(lds_read_col4<D>(qs, row0, col0, i16), lds_read_col4<D>(qs, row0 + 8, col0, i16));
+          dv[db] = mfma32(ado, pb[s2], dv[db]);
+          dk[db] = mfma32(aq, dsb[s2], dk[db]);
+        }
+      }
+    }
+    if (t + 1 < ntiles) {
+      char* qn = lds + ((t + 1) & 1) * 2 * TILE_BYTES;
+      ld.store(qn, qn + TILE_BYTES);
+      if (threadIdx.x < 2 * KT) rowterms[((t + 1) & 1) * 2 * KT + threadIdx.x] = rt;
+    }
+    __syncthreads();
+  }
+
+  if (live) {
+    float* krow = p.dk_rot + (bh * p.Nq + jc) * D;
+    float* vrow = p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        f32x4 wk, wv;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          wk[c] = dk[db][4 * rr + c] * p.scale;
+          wv[c] = dv[db][4 * rr + c];
+        }
+        *reinterpret_cast<f32x4*>(krow + 32 * db + 8 * rr + 4 * g) = wk;
+        *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
+      }
+  }
+}
+
+template <int D>
+hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
+                  float* dq_rot, float* dk_rot, float* dv, void* scratch, hipStream_t stream) {
+  BwdParams p;
+  p.q_rot = (const __bf16*)op.q_rot;
+  p.kc_rot = (const __bf16*)op.kc_rot;
+  p.v_chunk = (const __bf16*)op.v_chunk;
+  p.k_cache = (const __bf16*)op.k_cache;
+  p.v_cache = (const __bf16*)op.v_cache;
+  p.out = (const __bf16*)out;
+  p.dout = (const __bf16*)dout;
+  p.lse = lse;
+  p.delta = (float*)scratch;
+  p.dq_rot = dq_rot;
+  p.dk_rot = dk_rot;
+  p.dv = dv;
+  p.H = g.H;
+  p.Nq = op.Nq;
+  p.cache_rows = (int64_t)g.C * g.T;
+  p.scale = 1.0f / sqrtf((float)D);
+  p.scale_log2e = p.scale * kLog2e;
+  p.hist_rows = op.hist_rows;
+  const int64_t n_rows = (int64_t)g.B * op.Nq * g.H;
+  delta_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
+  constexpr int NQB = 2;
+  const int qtile = kWaves * 32 * NQB;
+  attn_bwd_dq_kernel<D, NQB><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+  const int ktile = kWaves * 32;
+  attn_bwd_dkv_kernel<D><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq) { return (size_t)g.B * g.H * Nq * sizeof(float); }
+
+hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse,
+                                const void* dout, float* dq_rot, float* dk_rot, float* dv, void* scratch,
+                                hipStream_t stream) {
+  if (g.D == 128) return launch<128>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch, stream);
+  return launch<64>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch, stream);
+}
+
+}  // namespace astro

@@ -1,0 +1,79 @@
+// Launch interfaces between the C-ABI layer and the HIP kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "../../include/astro.h"
+
+namespace astro {
+
+// Per-stream integers handed to kernels by value (the host tables are authoritative).
+struct StreamInts {
+  int32_t v[ASTRO_MAX_BATCH];
+};
+
+// Geometry and rotary tables every kernel needs.
+struct DevGeom {
+  int B, H, D, gh, gw, T, C, S;
+  int n_t, n_h, n_w;
+  const double* inv_freq_t;  // [n_t]  frequency of each temporal pair (fp64)
+  const float2* tab_h;       // [gh][n_h] (cos, sin) of row position * frequency
+  const float2* tab_w;       // [gw][n_w] (cos, sin) of column position * frequency
+};
+
+// Where a rotated / copied chunk tensor goes: head-major rows [B][H][rows_per_head][D];
+// frame i of stream b starts at row slot(b, i) * T when `ring` is set (slot from the
+// closed form over next_n), else at row i * T.
+struct ScatterDst {
+  void* a;
+  void* b;
+  int64_t rows_per_head;
+  int ring;
+};
+
+// a_in, b_in: [B, n_frames*T, H, D].  a is always rotated (if the geometry has rotary
+// pairs); b is rotated iff rotate_b.  first_frame.v[b] = absolute index of the chunk's
+// first frame, next_n.v[b] = its stream-local number.
+hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in,
+                               ScatterDst dst, bool rotate_b, int n_frames,
+                               const StreamInts& first_frame, const StreamInts& next_n,
+                               hipStream_t stream);
+
+// Inverse rotation of fp32 gradients: src head-major [B][H][n_frames*T][D] (rotated frame)
+// -> dst [B, n_frames*T, H, D] (un-rotated frame).
+hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* dst, int n_frames,
+                                     const StreamInts& first_frame, hipStream_t stream);
+
+// Keys / values visible to a chunk: the resident ring rows (a prefix of the ring) and
+// the chunk's own rows.
+struct AttnOperands {
+  const void* q_rot;    // [B][H][Nq][D] rotated queries (workspace)
+  const void* kc_rot;   // [B][H][Nq][D] rotated chunk keys (workspace)
+  const void* v_chunk;  // [B, Nq, H, D] caller's chunk values
+  const void* k_cache;  // [B][H][C*T][D]
+  const void* v_cache;  // [B][H][C*T][D]
+  int Nq;
+  StreamInts hist_rows;  // resident ring rows per stream
+};
+
+// ---- fp32 debug path -------------------------------------------------------
+size_t f32_fwd_workspace_floats(const DevGeom& g, int Nq);  // beyond q_rot / kc_rot
+size_t f32_bwd_workspace_floats(const DevGeom& g, int Nq);
+hipError_t launch_attn_fwd_f32(const DevGeom& g, const AttnOperands& op, float* out, float* lse,
+                               float* scratch, hipStream_t stream);
+hipError_t launch_attn_bwd_f32(const DevGeom& g, const AttnOperands& op, const float* out,
+                               const float* lse, const float* dout, float* dq_rot, float* dk_rot,
+                               float* dv, float* scratch, hipStream_t stream);
+
+// ---- bf16 MFMA path ----------------------------------------------------------
+hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse,
+                                hipStream_t stream);
+size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq);  // beyond q_rot / kc_rot
+hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out,
+                                const float* lse, const void* dout, float* dq_rot, float* dk_rot,
+                                float* dv, void* scratch, hipStream_t stream);
+
+}  // namespace astro

@@ -1,0 +1,166 @@
+// 3-axis rotary embedding fused with the layout change token-major -> head-major.
+// Used by the KV append (keys rotated into their ring slot, values copied; Sec. 3.2)
+// and by the attention pre-pass (queries and chunk keys rotated into the workspace).
+// HBM-bound: every element is read once and written once, 16 bytes per lane.
+#include "kernels.hpp"
+
+namespace astro {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kMaxBlockPairs = 64;  // n_t + n_h <= D/2 <= 64
+
+__device__ __forceinline__ int ring_slot(int n, int C, int S) {
+  return n < C ? n : S + (n - S) % (C - S);
+}
+
+// Block-constant (cos, sin): temporal pairs computed here in fp64 from the absolute
+// frame index, row pairs read from the table.
+__device__ __forceinline__ void fill_block_table(float2* tab, const DevGeom& g, int frame, int row) {
+  const int t = threadIdx.x;
+  if (t < g.n_t) {
+    double s, c;
+    sincos((double)frame * g.inv_freq_t[t], &s, &c);
+    tab[t] = make_float2((float)c, (float)s);
+  } else if (t < g.n_t + g.n_h) {
+    tab[t] = g.tab_h[row * g.n_h + (t - g.n_t)];
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ float2 pair_cs(const float2* tab, const DevGeom& g, int w, int pair) {
+  const int nb = g.n_t + g.n_h;
+  return pair < nb ? tab[pair] : g.tab_w[w * g.n_w + (pair - nb)];
+}
+
+// grid: x = n_frames * gh (frame in chunk, row), y = head, z = stream
+template <typename Elem, bool kRotateB>
+__global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const Elem* __restrict__ a_in,
+                                                                const Elem* __restrict__ b_in, Elem* __restrict__ a_out,
+                                                                Elem* __restrict__ b_out, int64_t rows_per_head, int ring,
+                                                                int n_frames, StreamInts first_frame, StreamInts next_n) {
+  constexpr int EPC = 16 / sizeof(Elem);  // elements per 16-byte chunk
+  __shared__ float2 tab[kMaxBlockPairs];
+  const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
+  if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+  const int cpr = g.D / EPC;  // chunks per token row of one head
+  const int dst_frame_row = ring ? ring_slot(next_n.v[b] + fi, g.C, g.S) * g.T : fi * g.T;
+  const int64_t in_tok0 = ((int64_t)b * n_frames + fi) * g.T + (int64_t)row * g.gw;
+  const int64_t out_row0 = ((int64_t)b * g.H + h) * rows_per_head + dst_frame_row + (int64_t)row * g.gw;
+  for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
+    const int w = idx / cpr, c = idx % cpr;
+    const int64_t in_off = ((in_tok0 + w) * g.H + h) * g.D + c * EPC;
+    const int64_t out_off = (out_row0 + w) * g.D + c * EPC;
+    if constexpr (sizeof(Elem) == 2) {
+      bf16x8 xa = *reinterpret_cast<const bf16x8*>(a_in + in_off);
+      bf16x8 xb = *reinterpret_cast<const bf16x8*>(b_in + in_off);
+      if (rope) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float2 cs = pair_cs(tab, g, w, c * 4 + u);
+          const float a0 = (float)xa[2 * u], a1 = (float)xa[2 * u + 1];
+          xa[2 * u] = (__bf16)(a0 * cs.x - a1 * cs.y);
+          xa[2 * u + 1] = (__bf16)(a0 * cs.y + a1 * cs.x);
+          if (kRotateB) {
+            const float b0 = (float)xb[2 * u], b1 = (float)xb[2 * u + 1];
+            xb[2 * u] = (__bf16)(b0 * cs.x - b1 * cs.y);
+            xb[2 * u + 1] = (__bf16)(b0 * cs.y + b1 * cs.x);
+          }
+        }
+      }
+      *reinterpret_cast<bf16x8*>(a_out + out_off) = xa;
+      *reinterpret_cast<bf16x8*>(b_out + out_off) = xb;
+    } else {
+      f32x4 xa = *reinterpret_cast<const f32x4*>(a_in + in_off);
+      f32x4 xb = *reinterpret_cast<const f32x4*>(b_in + in_off);
+      if (rope) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const float2 cs = pair_cs(tab, g, w, c * 2 + u);
+          const float a0 = xa[2 * u], a1 = xa[2 * u + 1];
+          xa[2 * u] = a0 * cs.x - a1 * cs.y;
+          xa[2 * u + 1] = a0 * cs.y + a1 * cs.x;
+          if (kRotateB) {
+            const float b0 = xb[2 * u], b1 = xb[2 * u + 1];
+            xb[2 * u] = b0 * cs.x - b1 * cs.y;
+            xb[2 * u + 1] = b0 * cs.y + b1 * cs.x;
+          }
+        }
+      }
+      *reinterpret_cast<f32x4*>(a_out + out_off) = xa;
+      *reinterpret_cast<f32x4*>(b_out + out_off) = xb;
+    }
+  }
+}
+
+// Gradient w.r.t. the un-rotated tensor = R(phi)^T * gradient w.r.t. the rotated one.
+__global__ void __launch_bounds__(kThreads) rope_unscatter_f32_kernel(DevGeom g, const float* __restrict__ src,
+                                                                      float* __restrict__ dst, int n_frames,
+                                                                      StreamInts first_frame) {
+  __shared__ float2 tab[kMaxBlockPairs];
+  const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
+  if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+  const int cpr = g.D / 4;
+  const int64_t tok0 = (int64_t)fi * g.T + (int64_t)row * g.gw;
+  const int64_t Nq = (int64_t)n_frames * g.T;
+  for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
+    const int w = idx / cpr, c = idx % cpr;
+    const int64_t src_off = (((int64_t)b * g.H + h) * Nq + tok0 + w) * g.D + c * 4;
+    const int64_t dst_off = (((int64_t)b * Nq + tok0 + w) * g.H + h) * g.D + c * 4;
+    f32x4 x = *reinterpret_cast<const f32x4*>(src + src_off);
+    if (rope) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float2 cs = pair_cs(tab, g, w, c * 2 + u);
+        const float x0 = x[2 * u], x1 = x[2 * u + 1];
+        x[2 * u] = x0 * cs.x + x1 * cs.y;
+        x[2 * u + 1] = -x0 * cs.y + x1 * cs.x;
+      }
+    }
+    *reinterpret_cast<f32x4*>(dst + dst_off) = x;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in, ScatterDst dst,
+                               bool rotate_b, int n_frames, const StreamInts& first_frame, const StreamInts& next_n,
+                               hipStream_t stream) {
+  dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
+  if (dtype == ASTRO_BF16) {
+    auto a = static_cast<const __bf16*>(a_in);
+    auto b = static_cast<const __bf16*>(b_in);
+    if (rotate_b)
+      rope_scatter_kernel<__bf16, true><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+    else
+      rope_scatter_kernel<__bf16, false><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
+                                                                    dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+  } else {
+    auto a = static_cast<const float*>(a_in);
+    auto b = static_cast<const float*>(b_in);
+    if (rotate_b)
+      rope_scatter_kernel<float, true><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
+                                                                  dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+    else
+      rope_scatter_kernel<float, false><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* dst, int n_frames,
+                                     const StreamInts& first_frame, hipStream_t stream) {
+  dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
+  rope_unscatter_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, n_frames, first_frame);
+  return hipGetLastError();
+}
+
+}  // namespace astro

@@ -1,0 +1,100 @@
+"""Shared helpers of the GPU parity tests: feed the HIP library and the fp64
+oracle the same seeded inputs in lockstep and compare."""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as wl
+from oracle import RollingCacheOracle
+
+# contract: max abs error on outputs and gradients for bf16 N(0,1) inputs
+BF16_ABS_TOL = 2e-2
+# the abs bound is larger than the signal at production key counts (outputs have
+# std ~ sqrt(e/Nk)), so errors are also gated relative to the reference's rms
+BF16_MAX_OVER_RMS = 6e-2
+BF16_RMS_OVER_RMS = 1e-2
+F32_ABS_TOL = 1e-5
+
+
+def dev_bf16(bits: np.ndarray, device="cuda:0"):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def dev_f32(x: np.ndarray, device="cuda:0"):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)
+
+
+def host_f64(t) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def err_stats(got: np.ndarray, ref: np.ndarray):
+    """(max abs err, max abs err / rms(ref), rms(err) / rms(ref)) over finite ref entries."""
+    mask = np.isfinite(ref)
+    assert mask.any()
+    e = got[mask] - ref[mask]
+    assert np.isfinite(e).all(), "non-finite values in the GPU result"
+    rms_ref = float(np.sqrt(np.mean(ref[mask] ** 2)))
+    return float(np.abs(e).max()), float(np.abs(e).max() / rms_ref), float(np.sqrt(np.mean(e ** 2)) / rms_ref)
+
+
+def assert_bf16_close(got, ref, what: str, report=None):
+    mx, mx_n, rms_n = err_stats(got, ref)
+    if report is not None:
+        report.append(f"{what}: max_abs={mx:.3e} max/rms={mx_n:.3e} rms/rms={rms_n:.3e}")
+    assert mx <= BF16_ABS_TOL, f"{what}: max abs err {mx} > {BF16_ABS_TOL}"
+    assert mx_n <= BF16_MAX_OVER_RMS, f"{what}: max err / rms(ref) = {mx_n}"
+    assert rms_n <= BF16_RMS_OVER_RMS, f"{what}: rms err / rms(ref) = {rms_n}"
+
+
+def assert_f32_close(got, ref, what: str):
+    mx, _, _ = err_stats(got, ref)
+    assert mx <= F32_ABS_TOL, f"{what}: max abs err {mx} > {F32_ABS_TOL}"
+
+
+class Lockstep:
+    """One GPU cache and one oracle fed the same frames."""
+
+    def __init__(self, w: wl.Workload, dtype="bf16", start_frames=None, max_chunk=None, device="cuda:0"):
+        import paper_2603_17051_amd as A
+        self.A = A
+        self.w = w
+        self.dtype = dtype
+        self.device = device
+        self.cache = A.astro_kvcache_create(
+            w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
+            max_chunk or w.chunk_frames, w.rope_pairs, w.rope_base,
+            A.ASTRO_BF16 if dtype == "bf16" else A.ASTRO_F32, device=device)
+        self.oracle = RollingCacheOracle(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames,
+                                         w.sink_frames, w.rope_pairs, w.rope_base, start_frames)
+        if start_frames is not None:
+            for b, s in enumerate(start_frames):
+                A.astro_kvcache_reset(self.cache, b, int(s))
+
+    # inputs are bf16 bit patterns (uint16) for dtype bf16, float32 arrays for f32
+    def dev(self, x):
+        return dev_bf16(x, self.device) if self.dtype == "bf16" else dev_f32(x, self.device)
+
+    def wide(self, x):
+        return wl.bf16_bits_to_f64(x) if self.dtype == "bf16" else np.asarray(x, dtype=np.float64)
+
+    def append(self, k, v, n_frames):
+        self.A.astro_kvcache_append(self.cache, self.dev(k), self.dev(v), n_frames)
+        self.oracle.append(self.wide(k), self.wide(v), n_frames)
+
+    def check_tables(self):
+        sf, sp, nn = self.A.astro_kvcache_tables(self.cache)
+        osf, osp, onn = self.oracle.table_arrays()
+        assert sf == osf.tolist(), (sf, osf.tolist())
+        assert sp == osp.tolist()
+        assert nn == onn.tolist()
+        return sf
+
+    def fwd(self, q, k, v, n_frames):
+        out, lse = self.A.astro_chunk_attn_fwd(self.cache, self.dev(q), self.dev(k), self.dev(v), n_frames)
+        return out, lse
+
+    def close(self):
+        self.cache.close()

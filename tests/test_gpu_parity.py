@@ -1,0 +1,284 @@
+"""GPU parity: the HIP library (through the C ABI) against the fp64 oracle on the
+same seeded inputs.  Contract: max abs error <= 2e-2 on outputs and gradients
+for bf16 N(0,1) inputs (<= 1e-5 on the fp32 debug path), integer tables
+bit-exact after every append; errors are also gated relative to rms(reference)
+because at production key counts the outputs are smaller than the abs bound."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import rope_angles, rope_rotate
+from helpers import (Lockstep, assert_bf16_close, assert_f32_close, dev_bf16, err_stats, host_f64)
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(lines):
+    for l in lines:
+        print("   ", l, flush=True)
+
+
+def check_cache_contents(ls: Lockstep, streams=None, heads=None):
+    """Every resident slot holds the rotated keys (to bf16 rounding) and the exact
+    values of the frame the tables say it holds."""
+    import torch
+    w = ls.w
+    T, C = w.tokens_per_frame, w.capacity_frames
+    sf, _, _ = ls.A.astro_kvcache_tables(ls.cache)
+    tdt = torch.bfloat16 if ls.dtype == "bf16" else torch.float32
+    kc = ls.cache.k_storage.view(tdt).view(w.batch, w.heads, C * T, w.head_dim)
+    vc = ls.cache.v_storage.view(tdt).view(w.batch, w.heads, C * T, w.head_dim)
+    for b in (range(w.batch) if streams is None else streams):
+        for slot, f in enumerate(sf[b]):
+            if f < 0:
+                continue
+            n = f - ls.oracle.start[b]
+            kf, vf = ls.oracle.history[b][n]
+            for h in (range(w.heads) if heads is None else heads):
+                ref_k = rope_rotate(np.asarray(kf[:, h:h + 1], dtype=np.float64), rope_angles(f, w.grid_h, w.grid_w, w.rope_pairs, w.rope_base))[:, 0]
+                got_k = host_f64(kc[b, h, slot * T:(slot + 1) * T])
+                got_v = host_f64(vc[b, h, slot * T:(slot + 1) * T])
+                tol = (2.0 ** -8 if ls.dtype == "bf16" else 2e-6) * np.abs(ref_k) + 1e-6
+                assert (np.abs(got_k - ref_k) <= tol).all(), (b, slot, h)
+                np.testing.assert_array_equal(got_v, np.asarray(vf[:, h], dtype=np.float64))
+
+
+# ---------------------------------------------------------------------------
+# fp32 debug path
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("D,pairs,C,S,Fc", [(64, (12, 10, 10), 4, 1, 2), (128, (22, 21, 21), 3, 0, 1), (64, (0, 0, 0), 2, 1, 1)])
+def test_f32_debug_path_streaming_fwd_bwd(D, pairs, C, S, Fc):
+    w = wl.Workload("f32_small", 11, 2, 2, D, 3, 5, C, S, Fc, 0, pairs)
+    ls = Lockstep(w, dtype="f32", start_frames=[3, 50])
+    shape = (w.batch, w.n_q, w.heads, w.head_dim)
+    for step in range(C + 3):
+        q, k, v, do = (wl.normal_f32(w.seed, t, shape, step) for t in (wl.T_Q, wl.T_K, wl.T_V, wl.T_DO))
+        out, lse = ls.fwd(q, k, v, Fc)
+        ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), Fc)
+        assert_f32_close(host_f64(out), ro, f"step {step} out")
+        assert_f32_close(host_f64(lse), rl, f"step {step} lse")
+        dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), Fc)
+        rq, rk, rv = ls.oracle.attn_bwd(ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), Fc)
+        assert_f32_close(host_f64(dq), rq, f"step {step} dq")
+        assert_f32_close(host_f64(dk), rk, f"step {step} dk")
+        assert_f32_close(host_f64(dv), rv, f"step {step} dv")
+        ls.append(k, v, Fc)
+        ls.check_tables()
+    check_cache_contents(ls)
+    ls.close()
+
+
+# ---------------------------------------------------------------------------
+# bf16 MFMA path, small shapes (whole tensors compared)
+# ---------------------------------------------------------------------------
+
+def test_bf16_tiny_fwd_full_ring():
+    """Batch 1, 2 heads, D 64, 8x8 frames, ring of 4 already full, one new frame."""
+    w = wl.TINY_FWD
+    ls = Lockstep(w)
+    pk, pv = wl.history_frame_pool(w, 4)
+    for n in range(4):
+        ls.append(pk[n][None], pv[n][None], 1)
+    ls.check_tables()
+    q, k, v = wl.chunk_inputs(w)
+    out, lse = ls.fwd(q, k, v, 1)
+    ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), 1)
+    rep = []
+    assert_bf16_close(host_f64(out), ro, "out", rep)
+    assert_bf16_close(host_f64(lse), rl, "lse", rep)
+    _report(rep)
+    check_cache_contents(ls)
+    ls.close()
+
+
+@pytest.mark.parametrize("D,pairs,gh,gw,B,H,C,S,Fc", [
+    (128, (22, 21, 21), 7, 9, 2, 3, 5, 1, 2),    # Nq = 126, keys up to 441: ragged query and key tails
+    (64, (12, 10, 10), 5, 13, 1, 2, 4, 0, 3),    # Nq = 195
+    (128, (22, 21, 21), 16, 20, 1, 2, 3, 1, 1),  # Nq = 320: more than one query tile
+    (128, (0, 0, 0), 4, 4, 1, 1, 2, 0, 1),       # no rotary, 16-token frames
+])
+def test_bf16_streaming_fwd_bwd_with_eviction(D, pairs, gh, gw, B, H, C, S, Fc):
+    w = wl.Workload("bf16_small", 12, B, H, D, gh, gw, C, S, Fc, 0, pairs)
+    ls = Lockstep(w, start_frames=[5 + 9 * b for b in range(B)])
+    rep = []
+    for step in range(C // Fc + 4):
+        q, k, v, do = wl.chunk_inputs(w, step, with_dout=True)
+        out, lse = ls.fwd(q, k, v, Fc)
+        ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), Fc)
+        assert_bf16_close(host_f64(out), ro, f"step {step} out", rep)
+        assert_bf16_close(host_f64(lse), rl, f"step {step} lse", rep)
+        dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), Fc)
+        rq, rk, rv = ls.oracle.attn_bwd(ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), Fc)
+        assert_bf16_close(host_f64(dq), rq, f"step {step} dq", rep)
+        assert_bf16_close(host_f64(dk), rk, f"step {step} dk", rep)
+        assert_bf16_close(host_f64(dv), rv, f"step {step} dv", rep)
+        ls.append(k, v, Fc)
+        ls.check_tables()
+    _report(rep[-5:])
+    check_cache_contents(ls)
+    ls.close()
+
+
+def test_bf16_first_chunk_on_empty_cache_and_single_frame_appends():
+    w = wl.Workload("bf16_empty", 13, 2, 2, 128, 6, 6, 3, 1, 2, 0, (22, 21, 21))
+    ls = Lockstep(w)
+    q, k, v = wl.chunk_inputs(w)
+    out, lse = ls.fwd(q, k, v, 2)  # keys = the chunk only
+    ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), 2)
+    assert_bf16_close(host_f64(out), ro, "out on empty cache")
+    # n_frames below max_chunk_frames
+    q1, k1, v1 = (x[:, :w.tokens_per_frame] for x in (q, k, v))
+    q1, k1, v1 = (np.ascontiguousarray(x) for x in (q1, k1, v1))
+    ls.append(k1, v1, 1)
+    out, lse = ls.fwd(q1, k1, v1, 1)
+    ro, rl = ls.oracle.attn_fwd(ls.wide(q1), ls.wide(k1), ls.wide(v1), 1)
+    assert_bf16_close(host_f64(out), ro, "one-frame chunk")
+    assert_bf16_close(host_f64(lse), rl, "one-frame chunk lse")
+    ls.close()
+
+
+def test_bad_calls_on_a_device_cache_are_rejected_before_launch():
+    import torch
+    import paper_2603_17051_amd as A
+    from paper_2603_17051_amd import binding
+    c = A.astro_kvcache_create(1, 2, 64, 4, 4, 3, 1, 2, (12, 10, 10))
+    x = torch.zeros(1, 32, 2, 64, dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.zeros(1, 2, 32, device="cuda:0")
+    fwd_b, bwd_b = A.astro_chunk_attn_workspace_bytes(c, 2)
+    ws = torch.zeros(fwd_b, dtype=torch.uint8, device="cuda:0")
+    lib = binding.library()
+    P = lambda t: t.data_ptr()
+    assert lib.astro_chunk_attn_fwd(c.handle, P(x), P(x), P(x), 3, P(x), P(lse), P(ws), fwd_b, None) == binding.ASTRO_ERR_INVALID_ARG
+    assert lib.astro_chunk_attn_fwd(c.handle, P(x), P(x), P(x), 2, P(x), P(lse), P(ws), fwd_b - 1, None) == binding.ASTRO_ERR_WORKSPACE
+    assert lib.astro_chunk_attn_fwd(c.handle, P(x), P(x), P(x), 2, P(x), P(lse), None, fwd_b, None) == binding.ASTRO_ERR_WORKSPACE
+    assert lib.astro_chunk_attn_fwd(c.handle, None, P(x), P(x), 2, P(x), P(lse), P(ws), fwd_b, None) == binding.ASTRO_ERR_INVALID_ARG
+    assert lib.astro_kvcache_append(c.handle, None, P(x), 2, None) == binding.ASTRO_ERR_INVALID_ARG
+    assert A.astro_kvcache_tables(c)[2] == [0]
+    torch.cuda.synchronize()
+    c.close()
+
+
+# ---------------------------------------------------------------------------
+# production shapes (sampled (stream, head) pairs computed in full by the oracle)
+# ---------------------------------------------------------------------------
+
+def _fill_history(ls, w, pool_k, pool_v, n_frames_each):
+    """Append pool frames to every stream, frame by frame, through the API."""
+    import torch
+    dk, dv = dev_bf16(pool_k), dev_bf16(pool_v)
+    fk, fv = wl.bf16_bits_to_f32(pool_k), wl.bf16_bits_to_f32(pool_v)  # oracle keeps views, no copies
+    npool = pool_k.shape[0]
+    for n in range(n_frames_each):
+        idx = [wl.pool_index(b, n, npool) for b in range(w.batch)]
+        it = torch.tensor(idx, device="cuda:0")
+        ls.A.astro_kvcache_append(ls.cache, dk.index_select(0, it).contiguous(), dv.index_select(0, it).contiguous(), 1)
+        for b in range(w.batch):
+            ls.oracle.append_stream(b, fk[idx[b]], fv[idx[b]], 1)
+
+
+def test_bf16_production_fwd_sampled_heads():
+    """12 heads, D 128, 30x52 frames, 18 cached frames + 3-frame chunk (4680 x 32760)."""
+    w = wl.PROD_FWD
+    ls = Lockstep(w, max_chunk=3, start_frames=[7])
+    pk, pv = wl.history_frame_pool(w, 6)
+    _fill_history(ls, w, pk, pv, 18)
+    ls.check_tables()
+    q, k, v = wl.chunk_inputs(w)
+    out, lse = ls.fwd(q, k, v, 3)
+    heads = [0, 5, 11]
+    qf, kf, vf = (wl.bf16_bits_to_f32(x) for x in (q, k, v))
+    ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, heads=heads)
+    rep = []
+    assert_bf16_close(host_f64(out), ro, "prod fwd out", rep)
+    assert_bf16_close(host_f64(lse), rl, "prod fwd lse", rep)
+    _report(rep)
+    check_cache_contents(ls, heads=[3])
+    ls.close()
+
+
+def test_bf16_grouped_streams_fwd_and_append():
+    """8 independent streams, each with its own ring phase and frame offset."""
+    w = wl.GROUP_FWD_APPEND
+    offs = wl.stream_offsets(w.seed, w.batch, 0, 60)
+    assert len(set((offs % w.capacity_frames).tolist())) > 2  # ring phases really differ
+    starts = [int(100 * b + 3) for b in range(w.batch)]
+    ls = Lockstep(w, max_chunk=3, start_frames=starts)
+    pk, pv = wl.history_frame_pool(w, 8)
+    import torch
+    dk, dv = dev_bf16(pk), dev_bf16(pv)
+    fk, fv = wl.bf16_bits_to_f32(pk), wl.bf16_bits_to_f32(pv)
+    total = int(offs.max()) + w.capacity_frames
+    # stream b is reset when exactly offs[b] + 18 appends remain, so it ends up having
+    # streamed offs[b] + 18 frames: the last 18 are resident, at ring phase offs[b] mod 18
+    for n in range(total):
+        for b in range(w.batch):
+            if total - n == int(offs[b]) + w.capacity_frames:
+                ls.A.astro_kvcache_reset(ls.cache, b, starts[b])
+                ls.oracle.reset(b, starts[b])
+        idx = [wl.pool_index(b, n, 8) for b in range(w.batch)]
+        it = torch.tensor(idx, device="cuda:0")
+        ls.A.astro_kvcache_append(ls.cache, dk.index_select(0, it).contiguous(), dv.index_select(0, it).contiguous(), 1)
+        for b in range(w.batch):
+            ls.oracle.append_stream(b, fk[idx[b]], fv[idx[b]], 1)
+    sf = ls.check_tables()
+    assert len({tuple(r) for r in sf}) > 2
+    q, k, v = wl.chunk_inputs(w)
+    out, lse = ls.fwd(q, k, v, 3)
+    qf, kf, vf = (wl.bf16_bits_to_f32(x) for x in (q, k, v))
+    rep = []
+    for b, h in [(0, 0), (3, 7), (7, 11)]:
+        ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, streams=[b], heads=[h])
+        assert_bf16_close(host_f64(out[b, :, h]), ro[b, :, h], f"stream {b} head {h} out", rep)
+        assert_bf16_close(host_f64(lse[b, h]), rl[b, h], f"stream {b} head {h} lse", rep)
+    _report(rep)
+    # the append half of the workload: commit the chunk, tables and contents follow
+    ls.append(k, v, 3)
+    ls.check_tables()
+    check_cache_contents(ls, streams=[2, 6], heads=[4])
+    ls.close()
+
+
+def test_bf16_long_stream_with_sink_and_eviction():
+    """Ring of 12 = 1 sink + 11 sliding slots, 40 sequential 3-frame chunks."""
+    w = wl.STREAM_EVICT
+    ls = Lockstep(w, start_frames=[0])
+    rep = []
+    for step in range(40):
+        q, k, v = wl.chunk_inputs(w, step)
+        out, lse = ls.fwd(q, k, v, 3)
+        h = step % w.heads
+        qf, kf, vf = (wl.bf16_bits_to_f32(x) for x in (q, k, v))
+        ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, heads=[h])
+        assert_bf16_close(host_f64(out[0, :, h]), ro[0, :, h], f"step {step} head {h} out", rep)
+        assert_bf16_close(host_f64(lse[0, h]), rl[0, h], f"step {step} head {h} lse", rep)
+        ls.oracle.append(kf, vf, 3)
+        ls.A.astro_kvcache_append(ls.cache, ls.dev(k), ls.dev(v), 3)
+        sf = ls.check_tables()
+        assert sf[0][0] == 0  # the sink frame stays
+        if step in (3, 4, 17, 39):
+            check_cache_contents(ls, heads=[h])
+        print(f"    step {step}: {rep[-2]}", flush=True)
+    ls.close()
+
+
+def test_bf16_rl_backward_sampled_pairs():
+    """Batch 4, 18 cached frames detached, 3-frame chunk: dQ, dK_chunk, dV_chunk in fp32."""
+    w = wl.RL_BWD
+    ls = Lockstep(w, max_chunk=3, start_frames=[11, 0, 29, 4])
+    pk, pv = wl.history_frame_pool(w, 6)
+    _fill_history(ls, w, pk, pv, 18)
+    q, k, v, do = wl.chunk_inputs(w, with_dout=True)
+    out, lse = ls.fwd(q, k, v, 3)
+    dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), 3)
+    qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in (q, k, v, do))
+    rep = []
+    for b, h in [(0, 2), (3, 9)]:
+        ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, streams=[b], heads=[h])
+        assert_bf16_close(host_f64(out[b, :, h]), ro[b, :, h], f"stream {b} head {h} out", rep)
+        rq, rk, rv = ls.oracle.attn_bwd(qf, kf, vf, dof, 3, streams=[b], heads=[h])
+        assert_bf16_close(host_f64(dq[b, :, h]), rq[b, :, h], f"stream {b} head {h} dq", rep)
+        assert_bf16_close(host_f64(dk[b, :, h]), rk[b, :, h], f"stream {b} head {h} dk", rep)
+        assert_bf16_close(host_f64(dv[b, :, h]), rv[b, :, h], f"stream {b} head {h} dv", rep)
+    _report(rep)
+    ls.close()
