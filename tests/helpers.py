@@ -11,8 +11,8 @@ from oracle import RollingCacheOracle
 BF16_ABS_TOL = 2e-2
 # the abs bound is larger than the signal at production key counts (outputs have
 # std ~ sqrt(e/Nk)), so errors are also gated relative to the reference's rms
-BF16_MAX_OVER_RMS = 6e-2
-BF16_RMS_OVER_RMS = 1e-2
+BF16_MAX_OVER_MAX = 3e-2   # max |err| / max |ref|
+BF16_RMS_OVER_RMS = 1e-2   # rms(err) / rms(ref)
 F32_ABS_TOL = 1e-5
 
 
@@ -31,21 +31,22 @@ def host_f64(t) -> np.ndarray:
 
 
 def err_stats(got: np.ndarray, ref: np.ndarray):
-    """(max abs err, max abs err / rms(ref), rms(err) / rms(ref)) over finite ref entries."""
+    """(max abs err, max abs err / max abs ref, rms(err) / rms(ref)) over finite ref entries."""
     mask = np.isfinite(ref)
     assert mask.any()
     e = got[mask] - ref[mask]
     assert np.isfinite(e).all(), "non-finite values in the GPU result"
     rms_ref = float(np.sqrt(np.mean(ref[mask] ** 2)))
-    return float(np.abs(e).max()), float(np.abs(e).max() / rms_ref), float(np.sqrt(np.mean(e ** 2)) / rms_ref)
+    max_ref = float(np.abs(ref[mask]).max())
+    return float(np.abs(e).max()), float(np.abs(e).max() / max_ref), float(np.sqrt(np.mean(e ** 2)) / rms_ref)
 
 
 def assert_bf16_close(got, ref, what: str, report=None):
     mx, mx_n, rms_n = err_stats(got, ref)
     if report is not None:
-        report.append(f"{what}: max_abs={mx:.3e} max/rms={mx_n:.3e} rms/rms={rms_n:.3e}")
+        report.append(f"{what}: max_abs={mx:.3e} max/max={mx_n:.3e} rms/rms={rms_n:.3e}")
     assert mx <= BF16_ABS_TOL, f"{what}: max abs err {mx} > {BF16_ABS_TOL}"
-    assert mx_n <= BF16_MAX_OVER_RMS, f"{what}: max err / rms(ref) = {mx_n}"
+    assert mx_n <= BF16_MAX_OVER_MAX, f"{what}: max err / max |ref| = {mx_n}"
     assert rms_n <= BF16_RMS_OVER_RMS, f"{what}: rms err / rms(ref) = {rms_n}"
 
 
