@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the rolling-cache chunk-attention hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input:
+chunk attention forward over the resident ring + the chunk, backward with the
+cached context detached, then the KV append of the chunk (rotary fused, ring
+eviction).  Inputs are resident in HBM before the timed region.  Prints ONE
+JSON line (metric, roofline of the dominant kernel, oracle timed on the host).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+
+
+def flops_fwd(w) -> float:
+    """4*Nq*Nk*D*H*B: the QK^T and PV contractions."""
+    return 4.0 * w.n_q * w.n_k * w.head_dim * w.heads * w.batch
+
+
+def flops_bwd(w) -> float:
+    """(6*Nq*Nk_cache + 10*Nq*Nq)*D*H*B: dP, dQ (+ S recompute counted once) over the
+    cached keys, all five contractions over the chunk's own keys; rotary, the second
+    S/dP recompute on chunk columns and staging are not counted."""
+    nk_cache = w.n_k - w.n_q
+    return (6.0 * w.n_q * nk_cache + 10.0 * w.n_q * w.n_q) * w.head_dim * w.heads * w.batch
+
+
+def append_bytes(w) -> float:
+    """read K, V + write K, V of the chunk (bf16); eviction moves nothing."""
+    return 4.0 * w.n_q * w.heads * w.head_dim * 2 * w.batch
+
+
+# algorithmic flops of one launch of each attention kernel
+def kernel_flops(name: str, w) -> float:
+    per = w.head_dim * w.heads * w.batch
+    if name == "attn_fwd_bf16":
+        return flops_fwd(w)
+    if name == "attn_bwd_dq_bf16":      # S, dP, dQ over all visible keys
+        return 6.0 * w.n_q * w.n_k * per
+    if name == "attn_bwd_dkv_bf16":     # dK, dV over the chunk's keys (its S/dP recompute not counted)
+        return 4.0 * w.n_q * w.n_q * per
+    return 0.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="rl_bwd")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (streams and heads shard "
+              "without any exchange, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2603_17051_amd as A
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    def make_cache(w):
+        cache = A.astro_kvcache_create(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames,
+                                       w.sink_frames, w.chunk_frames, w.rope_pairs, w.rope_base)
+        pk, pv = wl.history_frame_pool(w, 4)
+        dk, dv = dev_bf16(pk), dev_bf16(pv)
+        for n in range(min(w.resident_frames, w.capacity_frames)):
+            idx = torch.tensor([wl.pool_index(b, n, 4) for b in range(w.batch)], device=dev)
+            A.astro_kvcache_append(cache, dk.index_select(0, idx).contiguous(), dv.index_select(0, idx).contiguous(), 1)
+        return cache
+
+    # ---- main workload: fwd + bwd + append ---------------------------------------
+    cache = make_cache(w)
+    q, k, v, do = (dev_bf16(x) for x in wl.chunk_inputs(w, with_dout=True))
+    out = torch.empty_like(q)
+    lse = torch.empty((w.batch, w.heads, w.n_q), dtype=torch.float32, device=dev)
+    dq, dk_, dv_ = (torch.empty(q.shape, dtype=torch.float32, device=dev) for _ in range(3))
+    fwd_b, bwd_b = A.astro_chunk_attn_workspace_bytes(cache, w.chunk_frames)
+    ws = torch.empty(max(fwd_b, bwd_b), dtype=torch.uint8, device=dev)
+    Fc = w.chunk_frames
+
+    def step():
+        A.astro_chunk_attn_fwd(cache, q, k, v, Fc, out, lse, ws)
+        A.astro_chunk_attn_bwd(cache, q, k, v, out, lse, do, Fc, dq, dk_, dv_, ws)
+        A.astro_kvcache_append(cache, k, v, Fc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    step_flops = flops_fwd(w) + flops_bwd(w)
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel HIP-event timing over the same step (separate pass) ------------
+    A.astro_profile_begin()
+    for _ in range(args.steps):
+        step()
+    ktimes = A.astro_profile_end()
+    kernels = {}
+    for name, (launches, total_ms) in ktimes.items():
+        avg = total_ms / launches
+        ent = {"launches": launches, "avg_ms": round(avg, 4)}
+        fl = kernel_flops(name, w)
+        if fl:
+            ent["tflops"] = round(fl / (avg * 1e-3) / 1e12, 1)
+            ent["frac_bf16_mfma_peak"] = round(fl / (avg * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)
+        if name == "kv_append_rope":
+            ent["gbs"] = round(append_bytes(w) / (avg * 1e-3) / 1e9, 1)
+            ent["frac_hbm_peak"] = round(append_bytes(w) / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        kernels[name] = ent
+    dominant = max((n for n in ktimes if kernel_flops(n, w)), key=lambda n: ktimes[n][1])
+    d_avg = ktimes[dominant][1] / ktimes[dominant][0]
+    achieved = kernel_flops(dominant, w) / (d_avg * 1e-3) / 1e12
+    roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(d_avg, 4)}
+
+    result = {
+        "metric": "chunk-attn fwd+bwd TFLOP/s (algorithmic flops, bf16 MFMA, fp32 accumulate)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B{w.batch} H{w.heads} D{w.head_dim} T{w.tokens_per_frame} "
+                               f"ring {w.capacity_frames} frames full, chunk {w.chunk_frames} frames "
+                               f"(Nq={w.n_q}, Nk={w.n_k}); step = attn fwd + bwd (cache detached) + KV append",
+                   "flops_per_step": step_flops, "frac_bf16_mfma_peak": round(value / PEAK_BF16_MFMA_TFLOPS, 4)},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    cache.close()
+    del q, k, v, do, out, lse, dq, dk_, dv_, ws
+
+    # ---- extras: forward-only shapes and the append at batch 8 ----------------------
+    if not args.no_extras:
+        extras = {}
+        for name in ("prod_fwd", "group_fwd_append"):
+            we = wl.WORKLOADS[name]
+            ce = make_cache(we)
+            qe, ke, ve = (dev_bf16(x) for x in wl.chunk_inputs(we))
+            oe = torch.empty_like(qe)
+            le = torch.empty((we.batch, we.heads, we.n_q), dtype=torch.float32, device=dev)
+            wse = torch.empty(A.astro_chunk_attn_workspace_bytes(ce, we.chunk_frames)[0], dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+            torch.cuda.synchronize()
+            n = 20
+            t0 = time.perf_counter()
+            for _ in range(n):
+                A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / n
+            ent = {"fwd_ms": round(ms, 4), "fwd_tflops": round(flops_fwd(we) / (ms * 1e-3) / 1e12, 1),
+                   "frac_bf16_mfma_peak": round(flops_fwd(we) / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)}
+            if name == "group_fwd_append":
+                # rotate over distinct source buffers (> 256 MB in flight) so the append is not cache resident
+                srcs = [(dev_bf16(a), dev_bf16(b)) for a, b in
+                        (wl.chunk_inputs(we, step=s)[1:3] for s in range(1, 4))]
+                for i in range(3):
+                    A.astro_kvcache_append(ce, srcs[i % 3][0], srcs[i % 3][1], we.chunk_frames)
+                A.astro_profile_begin()
+                for i in range(18):
+                    A.astro_kvcache_append(ce, srcs[i % 3][0], srcs[i % 3][1], we.chunk_frames)
+                la, tot = A.astro_profile_end()["kv_append_rope"]
+                ent["append_ms"] = round(tot / la, 4)
+                ent["append_gbs"] = round(append_bytes(we) / (tot / la * 1e-3) / 1e9, 1)
+                ent["append_frac_hbm_peak"] = round(ent["append_gbs"] / PEAK_HBM_GBS, 4)
+                del srcs
+            extras[name] = ent
+            ce.close()
+            del qe, ke, ve, oe, le, wse
+        result["extras"] = extras
+
+    # ---- the fp64 oracle on the host cores, bounded sample of the same workload -----
+    if not args.no_cpu_baseline:
+        from oracle import RollingCacheOracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        orc = RollingCacheOracle(1, 1, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
+                                 w.rope_pairs, w.rope_base)
+        w1 = w.scaled(batch=1, heads=1)
+        pk, pv = wl.history_frame_pool(w1, 4)
+        fk, fv = wl.bf16_bits_to_f32(pk), wl.bf16_bits_to_f32(pv)
+        for n in range(min(w.resident_frames, w.capacity_frames)):
+            orc.append_stream(0, fk[n % 4], fv[n % 4], 1)
+        qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in wl.chunk_inputs(w1, with_dout=True))
+        t0 = time.perf_counter()
+        orc.attn_fwd(qf, kf, vf, w.chunk_frames)
+        orc.attn_bwd(qf, kf, vf, dof, w.chunk_frames)
+        sec = time.perf_counter() - t0
+        fl = flops_fwd(w1) + flops_bwd(w1)
+        result["cpu_baseline"] = {"value": round(fl / sec / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"one (stream, head) pair of the workload, forward + backward, "
+                                            f"{fl / 1e9:.1f} GFLOP algorithmic in {sec:.2f} s (fp64 numpy)"}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -139,6 +139,19 @@ int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_ch
                          float *dv_chunk, void *workspace, size_t workspace_bytes,
                          void *hip_stream);
 
+/* Measurement aid (Sec. 3.2 / 3.3 name no kernels; this times the library's own):
+ * between begin and end every kernel launch is bracketed by HIP events recorded on
+ * the stream it is launched on.  end() waits for those events (host-synchronous),
+ * aggregates by kernel name into out[0 .. *n_entries) (at most max_entries names)
+ * and switches timing off.  Process-wide, one host thread. */
+typedef struct astro_kernel_time {
+  char name[48];     /* kernel name, NUL-terminated */
+  int32_t launches;  /* launches seen                */
+  float total_ms;    /* summed event time            */
+} astro_kernel_time_t;
+int astro_profile_begin(void);
+int astro_profile_end(astro_kernel_time_t *out, int32_t max_entries, int32_t *n_entries);
+
 /* Static, never-NULL description of an error code. */
 const char *astro_strerror(int err);
 

@@ -30,6 +30,7 @@ EXPORTED = (
     "astro_kvcache_bytes", "astro_kvcache_create", "astro_kvcache_destroy", "astro_kvcache_reset",
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
+    "astro_profile_begin", "astro_profile_end",
 )
 
 
@@ -43,6 +44,10 @@ class astro_kvcache_desc_t(ctypes.Structure):
         ("rope_base", c_double),
         ("k_storage", c_void_p), ("v_storage", c_void_p),
     ]
+
+
+class astro_kernel_time_t(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", c_int32), ("total_ms", c_float)]
 
 
 class AstroError(RuntimeError):
@@ -69,6 +74,8 @@ def _load() -> ctypes.CDLL:
                                          c_void_p, c_size_t, c_void_p]
     lib.astro_chunk_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.astro_profile_begin.argtypes = []
+    lib.astro_profile_end.argtypes = [P(astro_kernel_time_t), c_int32, P(c_int32)]
     for name in EXPORTED:
         getattr(lib, name).restype = c_int
     lib.astro_strerror.argtypes = [c_int]
@@ -251,3 +258,15 @@ def astro_chunk_attn_bwd(cache: KVCache, q, k_chunk, v_chunk, out, lse, dout, n_
                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream(stream)), "astro_chunk_attn_bwd")
     return dq, dk_chunk, dv_chunk
+
+
+def astro_profile_begin() -> None:
+    _check(_lib.astro_profile_begin(), "astro_profile_begin")
+
+
+def astro_profile_end(max_entries: int = 32):
+    """{kernel name: (launches, total_ms)} of the launches since astro_profile_begin."""
+    buf = (astro_kernel_time_t * max_entries)()
+    n = c_int32(0)
+    _check(_lib.astro_profile_end(buf, max_entries, byref(n)), "astro_profile_end")
+    return {buf[i].name.decode(): (buf[i].launches, float(buf[i].total_ms)) for i in range(n.value)}

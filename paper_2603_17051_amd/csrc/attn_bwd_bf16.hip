@@ -354,12 +354,21 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   const int64_t n_rows = (int64_t)g.B * op.Nq * g.H;
-  delta_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
+  {
+    ProfileScope prof("attn_bwd_delta", stream);
+    delta_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
+  }
   constexpr int NQB = 2;
   const int qtile = kWaves * 32 * NQB;
-  attn_bwd_dq_kernel<D, NQB><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+  {
+    ProfileScope prof("attn_bwd_dq_bf16", stream);
+    attn_bwd_dq_kernel<D, NQB><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+  }
   const int ktile = kWaves * 32;
-  attn_bwd_dkv_kernel<D><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
+  {
+    ProfileScope prof("attn_bwd_dkv_bf16", stream);
+    attn_bwd_dkv_kernel<D><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
+  }
   return hipGetLastError();
 }
 

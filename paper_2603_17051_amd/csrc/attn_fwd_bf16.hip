@@ -207,6 +207,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.hist_rows = op.hist_rows;
   const int qtile = kWaves * 32 * NQB;
   dim3 grid((op.Nq + qtile - 1) / qtile, g.H, g.B);
+  ProfileScope prof("attn_fwd_bf16", stream);
   attn_fwd_bf16_kernel<D, NQB, OCC><<<grid, dim3(kThreads), 0, stream>>>(p);
   return hipGetLastError();
 }

@@ -10,6 +10,19 @@
 
 namespace astro {
 
+// Times the launches made during its lifetime when profiling is on (astro_profile_begin).
+class ProfileScope {
+ public:
+  ProfileScope(const char* name, hipStream_t stream);
+  ~ProfileScope();
+  ProfileScope(const ProfileScope&) = delete;
+  ProfileScope& operator=(const ProfileScope&) = delete;
+
+ private:
+  hipStream_t stream_;
+  int index_;
+};
+
 // Per-stream integers handed to kernels by value (the host tables are authoritative).
 struct StreamInts {
   int32_t v[ASTRO_MAX_BATCH];

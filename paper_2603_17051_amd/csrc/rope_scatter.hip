@@ -134,6 +134,7 @@ hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, co
                                bool rotate_b, int n_frames, const StreamInts& first_frame, const StreamInts& next_n,
                                hipStream_t stream) {
   dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
+  ProfileScope prof(dst.ring ? "kv_append_rope" : "chunk_rope_stage", stream);
   if (dtype == ASTRO_BF16) {
     auto a = static_cast<const __bf16*>(a_in);
     auto b = static_cast<const __bf16*>(b_in);
@@ -159,6 +160,7 @@ hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, co
 hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* dst, int n_frames,
                                      const StreamInts& first_frame, hipStream_t stream) {
   dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
+  ProfileScope prof("grad_rope_unstage", stream);
   rope_unscatter_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, n_frames, first_frame);
   return hipGetLastError();
 }
