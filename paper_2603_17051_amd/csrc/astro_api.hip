@@ -73,6 +73,11 @@ int check_chunk_call(const astro_kvcache* c, int n_frames) {
   if (c->geo.host_only) return ASTRO_ERR_BAD_STATE;
   if (n_frames < 1 || n_frames > c->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
   if (!c->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
+  // the kernels address one stream's chunk tensor and one head's ring with 32-bit byte offsets
+  const RingGeometry& g = c->geo;
+  const int64_t chunk_bytes = (int64_t)n_frames * g.T * g.H * g.D * 4;
+  const int64_t ring_bytes = (int64_t)g.C * g.T * g.D * 4;
+  if (chunk_bytes >= ((int64_t)1 << 31) || ring_bytes >= ((int64_t)1 << 31)) return ASTRO_ERR_UNSUPPORTED;
   return ASTRO_OK;
 }
 

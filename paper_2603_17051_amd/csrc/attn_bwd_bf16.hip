@@ -11,6 +11,8 @@
 // directly the B operand of the next, and the LDS tile of the other operand is read
 // either by rows (contraction over D) or through the transposing read (contraction over
 // the tile's rows).
+#include <cstdlib>
+
 #include "kernels.hpp"
 #include "mfma_common.hpp"
 
@@ -65,92 +67,58 @@ __global__ void __launch_bounds__(256) delta_kernel(BwdParams p, int64_t n_rows)
 
 // ---- dQ -----------------------------------------------------------------------
 template <int D, int NQB>
-__global__ void __launch_bounds__(kThreads, 1) attn_bwd_dq_kernel(BwdParams p) {
-  constexpr int QSTEPS = D / 16;
-  constexpr int DB = D / 32;
-  constexpr int TILE_BYTES = KT * D * 2;
-  __shared__ __attribute__((aligned(16))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
-
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i32 = lane & 31, g = lane >> 5, i16 = lane & 15, blk = (lane >> 4) & 1;
-  const int hist = p.hist_rows.v[b];
-  const int nk = hist + p.Nq;
-  const int ntiles = (nk + KT - 1) / KT;
-  const int q0 = (blockIdx.x * kWaves + wave) * 32 * NQB;
-  const int64_t bh = (int64_t)b * p.H + h;
-
-  // B operands held in registers: Q~ and dO rows of this lane's query
-  bf16x8 qreg[NQB][QSTEPS], doreg[NQB][QSTEPS];
+struct DqWave {
+  static constexpr int QSTEPS = D / 16;
+  static constexpr int DB = D / 32;
+  bf16x8 qreg[NQB][QSTEPS], doreg[NQB][QSTEPS];  // B operands: Q~ and dO rows of this lane's query
   float lse2[NQB], delta[NQB];
+  f32x16 dq[NQB][DB];
+  OperandAddr<D> addr;
+  int g;
+  float scale_log2e;
+
+  __device__ __forceinline__ void init(int lane, float sl2e) {
+    g = lane >> 5;
+    scale_log2e = sl2e;
+    addr.init(lane);
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int q = q0 + 32 * qb + i32;
-    const bool live = q < p.Nq;
-    const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
-    const __bf16* drow = p.dout + (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
+    for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) {
-      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
-      if (live) {
-        x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
-        y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
-      }
-      qreg[qb][st] = x;
-      doreg[qb][st] = y;
-    }
-    // a dead query row gets P = exp2(0 - big) = 0 everywhere
-    lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    delta[qb] = live ? p.delta[bh * p.Nq + q] : 0.f;
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
   }
 
-  f32x16 dq[NQB][DB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
-
-  const RowSource ksrc{p.k_cache + bh * p.cache_rows * D, D, hist, p.kc_rot + bh * p.Nq * D, D, p.Nq};
-  const RowSource vsrc{p.v_cache + bh * p.cache_rows * D, D, hist, p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D,
-                       (int64_t)p.H * D, p.Nq};
-  TilePairLoader<D, KT, kThreads> ld;
-  ld.load(ksrc, vsrc, 0);
-  ld.store(lds, lds + TILE_BYTES);
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
-    const char* ks = lds + (t & 1) * 2 * TILE_BYTES;
-    const char* vs = ks + TILE_BYTES;
-    if (t + 1 < ntiles) ld.load(ksrc, vsrc, t + 1);
-    const bool tail = (t + 1) * KT > nk;
-
+  // One 64-key tile.  Keys past the end of a segment need no masking here: their K rows
+  // are zero in LDS, so whatever dS they get contributes nothing to dQ~ = dS K~.
+  __device__ __forceinline__ void tile(const char* ks, const char* vs) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       f32x16 s[NQB], dp[NQB];
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
+      for (int st = 0; st < QSTEPS; ++st) {
+        const bf16x8 ak = read_rows8<D>(ks, addr.row[st], kb);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[qb][r] = 0.f, dp[qb][r] = 0.f;
+        for (int qb = 0; qb < NQB; ++qb) s[qb] = mfma32(ak, qreg[qb][st], st == 0 ? zero : s[qb]);
+      }
+      // keep the phases apart: hoisting every LDS read of a key block to its top costs
+      // more registers than two resident waves per SIMD have
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int st = 0; st < QSTEPS; ++st) {
-        const bf16x8 ak = lds_read_row8<D>(ks, 32 * kb + i32, 2 * st + g);
-        const bf16x8 av = lds_read_row8<D>(vs, 32 * kb + i32, 2 * st + g);
+        const bf16x8 av = read_rows8<D>(vs, addr.row[st], kb);
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          s[qb] = mfma32(ak, qreg[qb][st], s[qb]);
-          dp[qb] = mfma32(av, doreg[qb][st], dp[qb]);
-        }
+        for (int qb = 0; qb < NQB; ++qb) dp[qb] = mfma32(av, doreg[qb][st], st == 0 ? zero : dp[qb]);
       }
+      __builtin_amdgcn_sched_barrier(0);
       bf16x8 dsb[NQB][2];
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         float ds[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float pr = fast_exp2(fmaf(s[qb][r], p.scale_log2e, -lse2[qb]));
-          if (tail && t * KT + 32 * kb + acc_row(r, g) >= nk) pr = 0.f;
+          const float pr = fast_exp2(fmaf(s[qb][r], scale_log2e, -lse2[qb]));
           ds[r] = pr * (dp[qb][r] - delta[qb]);
         }
 #pragma unroll
@@ -158,23 +126,86 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dq_kernel(BwdParams p) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) dsb[qb][s2][j] = (__bf16)ds[8 * s2 + j];
       }
+      __builtin_amdgcn_sched_barrier(0);
       // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const int key0 = 32 * kb + 16 * s2 + 4 * g;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const int col0 = 32 * db + 16 * blk;
-          const bf16x8 a = concat4(lds_read_col4<D>(ks, key0, col0, i16), lds_read_col4<D>(ks, key0 + 8, col0, i16));
+          const bf16x8 a = read_cols8<D>(ks, addr.tr[db], 32 * kb + 16 * s2);
 #pragma unroll
           for (int qb = 0; qb < NQB; ++qb) dq[qb][db] = mfma32(a, dsb[qb][s2], dq[qb][db]);
         }
       }
     }
-    if (t + 1 < ntiles) {
-      char* kn = lds + ((t + 1) & 1) * 2 * TILE_BYTES;
-      ld.store(kn, kn + TILE_BYTES);
+  }
+};
+
+template <int D, int NQB, int OCC>
+__global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p) {
+  using Wave = DqWave<D, NQB>;
+  constexpr int TILE_BYTES = KT * D * 2;
+  __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i32 = lane & 31, g = lane >> 5;
+  const int hist = p.hist_rows.v[b];
+  const int hist_tiles = (hist + KT - 1) / KT;
+  const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
+  const int q0 = (blockIdx.x * kWaves + wave) * 32 * NQB;
+  const int64_t bh = (int64_t)b * p.H + h;
+
+  Wave w;
+  w.init(lane, p.scale_log2e);
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int q = q0 + 32 * qb + i32;
+    const bool live = q < p.Nq;
+    const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
+    const __bf16* drow = p.dout + (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
+#pragma unroll
+    for (int st = 0; st < Wave::QSTEPS; ++st) {
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
+      if (live) {
+        x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
+        y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
+      }
+      w.qreg[qb][st] = x;
+      w.doreg[qb][st] = y;
     }
+    // a dead query row gets P = exp2(0 - big) = 0 everywhere
+    w.lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    w.delta[qb] = live ? p.delta[bh * p.Nq + q] : 0.f;
+  }
+
+  const RowSegment k_hist = make_segment(p.k_cache + bh * p.cache_rows * D, D, hist, D);
+  const RowSegment v_hist = make_segment(p.v_cache + bh * p.cache_rows * D, D, hist, D);
+  const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
+  const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
+  TileStreamer<D, KT, kWaves> ts;
+  ts.init();
+  const uint32_t off_dense = ts.lane_offset(k_hist);
+  const uint32_t off_vchunk = ts.lane_offset(v_chunk);
+  auto issue = [&](int t) {
+    char* kbuf = lds + (t & 1) * 2 * TILE_BYTES;
+    if (t < hist_tiles) {
+      ts.issue(k_hist, off_dense, t * KT, kbuf);
+      ts.issue(v_hist, off_dense, t * KT, kbuf + TILE_BYTES);
+    } else {
+      ts.issue(k_chunk, off_dense, (t - hist_tiles) * KT, kbuf);
+      ts.issue(v_chunk, off_vchunk, (t - hist_tiles) * KT, kbuf + TILE_BYTES);
+    }
+  };
+  issue(0);
+  wait_vmem();
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    if (t + 1 < ntiles) issue(t + 1);
+    const char* kbuf = lds + (t & 1) * 2 * TILE_BYTES;
+    w.tile(kbuf, kbuf + TILE_BYTES);
+    wait_vmem();
     __syncthreads();
   }
 
@@ -184,13 +215,13 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dq_kernel(BwdParams p) {
     if (q < p.Nq) {
       float* row = p.dq_rot + (bh * p.Nq + q) * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < Wave::DB; ++db)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          f32x4 w;
+          f32x4 x;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) w[c] = dq[qb][db][4 * rr + c] * p.scale;
-          *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = w;
+          for (int c = 0; c < 4; ++c) x[c] = w.dq[qb][db][4 * rr + c] * p.scale;
+          *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
         }
     }
   }
@@ -198,84 +229,36 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dq_kernel(BwdParams p) {
 
 // ---- dK, dV of the chunk's keys ---------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(kThreads, 1) attn_bwd_dkv_kernel(BwdParams p) {
-  constexpr int QSTEPS = D / 16;
-  constexpr int DB = D / 32;
-  constexpr int TILE_BYTES = KT * D * 2;
-  // Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [KT] and Delta [KT]
-  __shared__ __attribute__((aligned(16))) char lds[4 * TILE_BYTES + 4 * KT * 4];
-  float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
-
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i32 = lane & 31, g = lane >> 5, i16 = lane & 15, blk = (lane >> 4) & 1;
-  const int64_t bh = (int64_t)b * p.H + h;
-  const int jc = (blockIdx.x * kWaves + wave) * 32 + i32;  // this lane's chunk key
-  const bool live = jc < p.Nq;
-  const int ntiles = (p.Nq + KT - 1) / KT;
-
-  bf16x8 kreg[QSTEPS], vreg[QSTEPS];
-  {
-    const __bf16* krow = p.kc_rot + (bh * p.Nq + (live ? jc : 0)) * D;
-    const __bf16* vrow = p.v_chunk + (((int64_t)b * p.Nq + (live ? jc : 0)) * p.H + h) * D;
-#pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) {
-      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
-      if (live) {
-        x = *reinterpret_cast<const bf16x8*>(krow + st * 16 + g * 8);
-        y = *reinterpret_cast<const bf16x8*>(vrow + st * 16 + g * 8);
-      }
-      kreg[st] = x;
-      vreg[st] = y;
-    }
-  }
+struct DkvWave {
+  static constexpr int QSTEPS = D / 16;
+  static constexpr int DB = D / 32;
+  bf16x8 kreg[QSTEPS], vreg[QSTEPS];  // B operands: K~ and V rows of this lane's chunk key
   f32x16 dk[DB], dv[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dk[db][r] = 0.f, dv[db][r] = 0.f;
+  OperandAddr<D> addr;
+  int g;
+  float scale_log2e;
 
-  const RowSource qsrc{p.q_rot + bh * p.Nq * D, D, p.Nq, nullptr, 0, 0};
-  const RowSource dsrc{p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, nullptr, 0, 0};
-  TilePairLoader<D, KT, kThreads> ld;
-  float rt = 0.f;  // thread < KT: LSE*log2e of row `thread`; KT <= thread < 2KT: Delta
-  auto load_rowterm = [&](int tile) {
-    const int t = threadIdx.x;
-    if (t < 2 * KT) {
-      const int q = tile * KT + (t & (KT - 1));
-      // rows past Nq: P = exp2(0 - big) = 0
-      if (t < KT) rt = q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-      else rt = q < p.Nq ? p.delta[bh * p.Nq + q] : 0.f;
-    }
-  };
-  ld.load(qsrc, dsrc, 0);
-  load_rowterm(0);
-  ld.store(lds, lds + TILE_BYTES);
-  if (threadIdx.x < 2 * KT) rowterms[threadIdx.x] = rt;
-  __syncthreads();
+  __device__ __forceinline__ void init(int lane, float sl2e) {
+    g = lane >> 5;
+    scale_log2e = sl2e;
+    addr.init(lane);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dk[db][r] = 0.f, dv[db][r] = 0.f;
+  }
 
-  for (int t = 0; t < ntiles; ++t) {
-    const char* qs = lds + (t & 1) * 2 * TILE_BYTES;
-    const char* dos = qs + TILE_BYTES;
-    const float* lse_t = rowterms + (t & 1) * 2 * KT;
-    const float* delta_t = lse_t + KT;
-    if (t + 1 < ntiles) {
-      ld.load(qsrc, dsrc, t + 1);
-      load_rowterm(t + 1);
-    }
+  // One tile of 64 queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, const float* delta_t) {
 #pragma unroll
     for (int qb = 0; qb < KT / 32; ++qb) {
       // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       f32x16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+      for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(qs, addr.row[st], qb), kreg[st], st == 0 ? zero : s);
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) {
-        const bf16x8 aq = lds_read_row8<D>(qs, 32 * qb + i32, 2 * st + g);
-        const bf16x8 ad = lds_read_row8<D>(dos, 32 * qb + i32, 2 * st + g);
-        s = mfma32(aq, kreg[st], s);
-        dp = mfma32(ad, vreg[st], dp);
-      }
+      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
       bf16x8 pb[2], dsb[2];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
@@ -284,7 +267,7 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dkv_kernel(BwdParams p) 
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int r = 4 * rr + c;
-          const float pr = fast_exp2(fmaf(s[r], p.scale_log2e, -l4[c]));
+          const float pr = fast_exp2(fmaf(s[r], scale_log2e, -l4[c]));
           const float ds = pr * (dp[r] - d4[c]);
           pb[r >> 3][r & 7] = (__bf16)pr;
           dsb[r >> 3][r & 7] = (__bf16)ds;
@@ -293,22 +276,84 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dkv_kernel(BwdParams p) 
       // dV^T[d][key] += dO^T[d][q] P[q][key];  dK~^T[d][key] += Q~^T[d][q] dS[q][key]
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const int row0 = 32 * qb + 16 * s2 + 4 * g;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const int col0 = 32 * db + 16 * blk;
-          const bf16x8 ado = concat4(lds_read_col4<D>(dos, row0, col0, i16), lds_read_col4<D>(dos, row0 + 8, col0, i16));
-          const bf16x8 aq = concat4(lds_read_col4<D>(qs, row0, col0, i16), lds_read_col4<D>(qs, row0 + 8, col0, i16));
-          dv[db] = mfma32(ado, pb[s2], dv[db]);
-          dk[db] = mfma32(aq, dsb[s2], dk[db]);
+          dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
+          dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
         }
       }
     }
-    if (t + 1 < ntiles) {
-      char* qn = lds + ((t + 1) & 1) * 2 * TILE_BYTES;
-      ld.store(qn, qn + TILE_BYTES);
-      if (threadIdx.x < 2 * KT) rowterms[((t + 1) & 1) * 2 * KT + threadIdx.x] = rt;
+  }
+};
+
+template <int D, int OCC>
+__global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p) {
+  using Wave = DkvWave<D>;
+  constexpr int TILE_BYTES = KT * D * 2;
+  // Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [KT] and Delta [KT]
+  __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES + 4 * KT * 4];
+  float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i32 = lane & 31, g = lane >> 5;
+  const int64_t bh = (int64_t)b * p.H + h;
+  const int jc = (blockIdx.x * kWaves + wave) * 32 + i32;  // this lane's chunk key
+  const bool live = jc < p.Nq;
+  const int ntiles = (p.Nq + KT - 1) / KT;
+
+  Wave w;
+  w.init(lane, p.scale_log2e);
+  {
+    const __bf16* krow = p.kc_rot + (bh * p.Nq + (live ? jc : 0)) * D;
+    const __bf16* vrow = p.v_chunk + (((int64_t)b * p.Nq + (live ? jc : 0)) * p.H + h) * D;
+#pragma unroll
+    for (int st = 0; st < Wave::QSTEPS; ++st) {
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
+      if (live) {
+        x = *reinterpret_cast<const bf16x8*>(krow + st * 16 + g * 8);
+        y = *reinterpret_cast<const bf16x8*>(vrow + st * 16 + g * 8);
+      }
+      w.kreg[st] = x;
+      w.vreg[st] = y;
     }
+  }
+
+  const RowSegment q_rows = make_segment(p.q_rot + bh * p.Nq * D, D, p.Nq, D);
+  const RowSegment do_rows = make_segment(p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
+  TileStreamer<D, KT, kWaves> ts;
+  ts.init();
+  const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
+  // thread < KT carries LSE*log2e of tile row `thread`, KT <= thread < 2KT its Delta;
+  // rows past Nq get P = exp2(0 - big) = 0
+  auto rowterm = [&](int tile) {
+    const int t = threadIdx.x;
+    const int q = tile * KT + (t & (KT - 1));
+    if (t < KT) return q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    return (t < 2 * KT && q < p.Nq) ? p.delta[bh * p.Nq + q] : 0.f;
+  };
+  auto issue = [&](int t) {
+    char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
+    ts.issue(q_rows, off_q, t * KT, qbuf);
+    ts.issue(do_rows, off_do, t * KT, qbuf + TILE_BYTES);
+  };
+  issue(0);
+  if (threadIdx.x < 2 * KT) rowterms[threadIdx.x] = rowterm(0);
+  wait_vmem();
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const bool more = t + 1 < ntiles;
+    float rt = 0.f;
+    if (more) {
+      issue(t + 1);
+      rt = rowterm(t + 1);
+    }
+    const char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
+    const float* terms = rowterms + (t & 1) * 2 * KT;
+    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + KT);
+    if (more && threadIdx.x < 2 * KT) rowterms[((t + 1) & 1) * 2 * KT + threadIdx.x] = rt;
+    wait_vmem();
     __syncthreads();
   }
 
@@ -316,19 +361,29 @@ __global__ void __launch_bounds__(kThreads, 1) attn_bwd_dkv_kernel(BwdParams p) 
     float* krow = p.dk_rot + (bh * p.Nq + jc) * D;
     float* vrow = p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < Wave::DB; ++db)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         f32x4 wk, wv;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          wk[c] = dk[db][4 * rr + c] * p.scale;
-          wv[c] = dv[db][4 * rr + c];
+          wk[c] = w.dk[db][4 * rr + c] * p.scale;
+          wv[c] = w.dv[db][4 * rr + c];
         }
         *reinterpret_cast<f32x4*>(krow + 32 * db + 8 * rr + 4 * g) = wk;
         *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
       }
   }
+}
+
+// tuning knob (environment ASTRO_BWD_VARIANT): 0 = 32 queries per wave and two workgroups per
+// CU in the dQ kernel, 1 = 64 queries per wave and one workgroup per CU
+int bwd_variant() {
+  static const int v = [] {
+    const char* e = getenv("ASTRO_BWD_VARIANT");
+    return e ? atoi(e) : 0;
+  }();
+  return v;
 }
 
 template <int D>
@@ -358,16 +413,20 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
     ProfileScope prof("attn_bwd_delta", stream);
     delta_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
   }
-  constexpr int NQB = 2;
-  const int qtile = kWaves * 32 * NQB;
   {
     ProfileScope prof("attn_bwd_dq_bf16", stream);
-    attn_bwd_dq_kernel<D, NQB><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+    if (bwd_variant() == 1) {
+      const int qtile = kWaves * 32 * 2;
+      attn_bwd_dq_kernel<D, 2, 1><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+    } else {
+      const int qtile = kWaves * 32;
+      attn_bwd_dq_kernel<D, 1, 2><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+    }
   }
   const int ktile = kWaves * 32;
   {
     ProfileScope prof("attn_bwd_dkv_bf16", stream);
-    attn_bwd_dkv_kernel<D><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
+    attn_bwd_dkv_kernel<D, 1><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
   }
   return hipGetLastError();
 }

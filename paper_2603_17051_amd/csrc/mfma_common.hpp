@@ -45,6 +45,7 @@ __device__ __forceinline__ float sum_with_partner32(float x) {
 // position c ^ swizzle(r) so that both access patterns of the kernels spread over the
 // banks: 32 lanes reading one chunk column of 32 consecutive rows (row operand of a
 // QK-type product), and the transposing read of 8 consecutive rows x 4 chunks.
+// swizzle(r) depends on r mod 16 only.
 template <int CPR>
 __device__ __forceinline__ int swizzle(int row) {
   if constexpr (CPR == 16)
@@ -58,23 +59,13 @@ __device__ __forceinline__ int lds_chunk_offset(int row, int chunk) {  // in byt
   return (row * CPR + (chunk ^ swizzle<CPR>(row))) * 16;
 }
 
-// 8 contiguous bf16 of one row: element columns 8*chunk .. 8*chunk+7.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_read_row8(const char* tile, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + lds_chunk_offset<D>(row, chunk));
-}
-
 // Transposing read (ds_read_b64_tr_b16): within each block of 16 lanes the lanes
 // 4r .. 4r+3 together supply row r (16 values) of a 4x16 matrix, and lane i receives
 // column i.  With lane i pointing at tile[row0 + i/4][col0 + 4*(i%4) ..] it returns
 // tile[row0 + 0..3][col0 + i]: four consecutive ROWS of one column.
-template <int D>
-__device__ __forceinline__ bf16x4 lds_read_col4(const char* tile, int row0, int col0, int lane16) {
-  const int row = row0 + (lane16 >> 2);
-  const int col = col0 + 4 * (lane16 & 3);
-  const int off = lds_chunk_offset<D>(row, col >> 3) + (col & 7) * 2;
+__device__ __forceinline__ bf16x4 lds_read_tr4(const char* lane_ptr) {
   typedef i16x4 __attribute__((address_space(3))) * lds_ptr;
-  i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + off));
+  i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lane_ptr));
   return __builtin_bit_cast(bf16x4, v);
 }
 
@@ -84,52 +75,100 @@ __device__ __forceinline__ bf16x8 concat4(bf16x4 a, bf16x4 b) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// ---- global -> LDS staging of [TILE rows][D] bf16 tiles -------------------------------
-// A tile's rows come from up to two row-major sources laid end to end (the resident ring
-// rows, then the chunk's rows); rows past both are zero-filled.
-struct RowSource {
-  const __bf16* base0;
-  int64_t stride0;  // elements between rows
-  int n0;
-  const __bf16* base1;
-  int64_t stride1;
-  int n1;
+// sum of the two bf16 halves of a packed pair, added to acc (v_dot2_f32_bf16 with ones)
+__device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
+}
+
+// Per-lane LDS byte offsets of the two operand access patterns of a [rows][D] tile, for
+// the first 32-row block / first 16 rows; further blocks are constant offsets because
+// the swizzle has period 16 rows.
+template <int D>
+struct OperandAddr {
+  static constexpr int QSTEPS = D / 16;
+  static constexpr int DB = D / 32;
+  uint32_t row[QSTEPS];  // 8 contiguous columns 16*st + 8g .. of row (lane % 32): A operand, contraction over D
+  uint32_t tr[DB][2];    // transposing read: rows 4g + 8*half + 0..3 of column 32*db + lane % 32
+
+  __device__ __forceinline__ void init(int lane) {
+    const int i32 = lane & 31, i16 = lane & 15, blk = (lane >> 4) & 1, g = lane >> 5;
+#pragma unroll
+    for (int st = 0; st < QSTEPS; ++st) row[st] = lds_chunk_offset<D>(i32, 2 * st + g);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int r = 4 * g + 8 * half + (i16 >> 2);
+        const int c = 32 * db + 16 * blk + 4 * (i16 & 3);
+        tr[db][half] = lds_chunk_offset<D>(r, c >> 3) + (c & 7) * 2;
+      }
+  }
 };
 
-template <int D, int TILE, int THREADS>
-struct TilePairLoader {
-  static constexpr int CPR = D / 8;
-  static constexpr int kChunks = TILE * CPR / THREADS;  // 16-byte chunks per thread per tile
-  static_assert(TILE * CPR % THREADS == 0, "tile must divide over the threads");
-  u32x4 a[kChunks], b[kChunks];
+template <int D>
+__device__ __forceinline__ bf16x8 read_rows8(const char* tile, uint32_t addr, int block32) {
+  return *reinterpret_cast<const bf16x8*>(tile + addr + block32 * 32 * D * 2);
+}
+// A operand of a product contracting over 16 tile rows starting at row16 (a multiple of 16):
+// k-slots 8g .. 8g+3 <- rows row16 + 4g + 0..3, k-slots 8g+4 .. 8g+7 <- rows row16 + 8 + 4g + 0..3,
+// the same row order in which a 32x32 accumulator hands over its registers 8*(row16/16 % 2) ..
+template <int D>
+__device__ __forceinline__ bf16x8 read_cols8(const char* tile, const uint32_t (&addr)[2], int row16) {
+  return concat4(lds_read_tr4(tile + addr[0] + row16 * D * 2), lds_read_tr4(tile + addr[1] + row16 * D * 2));
+}
 
-  __device__ __forceinline__ static u32x4 fetch(const RowSource& s, int j, int c) {
-    u32x4 x = {0, 0, 0, 0};
-    if (j < s.n0)
-      x = *reinterpret_cast<const u32x4*>(s.base0 + (int64_t)j * s.stride0 + c * 8);
-    else if (j < s.n0 + s.n1)
-      x = *reinterpret_cast<const u32x4*>(s.base1 + (int64_t)(j - s.n0) * s.stride1 + c * 8);
-    return x;
+// ---- global -> LDS streaming of [TILE rows][D] bf16 tiles -------------------------------
+// Tiles are copied by direct-to-LDS buffer loads (16 bytes per lane, no registers): one
+// wave instruction fills 1 KB of consecutive LDS, lane i the 16 bytes at i*16, so the lane
+// owning physical chunk p of row r fetches logical chunk p ^ swizzle(r) of that row.
+// A row source is a raw buffer descriptor whose size ends with its last valid row: rows
+// past the end read as zeros (written to LDS as zeros) without touching memory.
+struct RowSegment {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t stride_bytes;
+};
+
+__device__ __forceinline__ RowSegment make_segment(const __bf16* base, int64_t stride_elems, int n_rows, int D) {
+  RowSegment s;
+  const int64_t bytes = n_rows > 0 ? (int64_t)(n_rows - 1) * stride_elems * 2 + D * 2 : 0;
+  s.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+  s.stride_bytes = (uint32_t)(stride_elems * 2);
+  return s;
+}
+
+template <int D, int TILE, int WAVES>
+struct TileStreamer {
+  static constexpr int CPR = D / 8;                    // 16-byte chunks per row
+  static constexpr int kRowsPerInst = 64 / CPR;        // rows one wave instruction covers
+  static constexpr int kInsts = TILE / (kRowsPerInst * WAVES);
+  static_assert(TILE % (kRowsPerInst * WAVES) == 0, "tile must divide over the waves");
+  int wave, lane_row, lane_chunk_bytes;
+
+  __device__ __forceinline__ void init() {
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    lane_row = wave * kRowsPerInst + lane / CPR;  // row within the first pass of the tile
+    lane_chunk_bytes = ((lane % CPR) ^ swizzle<CPR>(lane_row)) * 16;
   }
-  __device__ __forceinline__ void load(const RowSource& sa, const RowSource& sb, int tile) {
-#pragma unroll
-    for (int u = 0; u < kChunks; ++u) {
-      const int cid = threadIdx.x + u * THREADS;
-      const int row = cid / CPR, c = cid % CPR;
-      a[u] = fetch(sa, tile * TILE + row, c);
-      b[u] = fetch(sb, tile * TILE + row, c);
-    }
+  // per-lane byte offset of its row/chunk inside a tile of a source with this stride
+  __device__ __forceinline__ uint32_t lane_offset(const RowSegment& s) const {
+    return (uint32_t)lane_row * s.stride_bytes + (uint32_t)lane_chunk_bytes;
   }
-  __device__ __forceinline__ void store(char* lds_a, char* lds_b) const {
+  // Start copying rows [row0, row0 + TILE) of `s` into the LDS tile (asynchronous; complete
+  // after s_waitcnt vmcnt(0) + barrier).  row0 must be wave-uniform.
+  __device__ __forceinline__ void issue(const RowSegment& s, uint32_t lane_off, int row0, char* lds_tile) const {
+    typedef __attribute__((address_space(3))) void* lds_ptr;
 #pragma unroll
-    for (int u = 0; u < kChunks; ++u) {
-      const int cid = threadIdx.x + u * THREADS;
-      const int row = cid / CPR, c = cid % CPR;
-      const int off = lds_chunk_offset<D>(row, c);
-      *reinterpret_cast<u32x4*>(lds_a + off) = a[u];
-      *reinterpret_cast<u32x4*>(lds_b + off) = b[u];
+    for (int u = 0; u < kInsts; ++u) {
+      const uint32_t rows = (uint32_t)(row0 + u * WAVES * kRowsPerInst);
+      char* dst = lds_tile + (u * WAVES + wave) * kRowsPerInst * D * 2;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(s.rsrc, (lds_ptr)dst, 16, (int)(rows * s.stride_bytes + lane_off), 0, 0, 0);
     }
   }
 };
+
+// wait until this wave's outstanding global loads (including direct-to-LDS ones) are done
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
 }  // namespace astro
