@@ -65,7 +65,7 @@ __global__ void softmax_kernel(F32Operands p, float* s, float* lse) {
   const int bh = blockIdx.y, b = bh / p.H, q = blockIdx.x;
   const int nk = p.hist_rows.v[b] + p.Nq;
   float* row = score_row(s, p, bh, q);
-  float m = -INFINITY;
+  float m = -3.0e38f;
   for (int j = threadIdx.x; j < nk; j += blockDim.x) m = fmaxf(m, row[j]);
   m = block_reduce(m, true, red);
   float z = 0.f;

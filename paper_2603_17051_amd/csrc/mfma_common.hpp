@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 namespace astro {
 
@@ -170,5 +171,11 @@ struct TileStreamer {
 
 // wait until this wave's outstanding global loads (including direct-to-LDS ones) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
+// ... all but the N most recently issued ones (loads complete in issue order)
+template <int N>
+__device__ __forceinline__ void wait_vmem_except() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
+}
 
 }  // namespace astro
