@@ -36,7 +36,7 @@ struct BwdParams {
   float* dq_rot;  // [B][H][Nq][D]
   float* dk_rot;  // [B][H][Nq][D]
   float* dv;      // [B, Nq, H, D]
-  int H, Nq;
+  int H, Nq, BH, tiles;  // tiles = workgroups per (stream, head) of the kernel being launched
   int64_t cache_rows;
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -147,13 +147,15 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   constexpr int TILE_BYTES = KT * D * 2;
   __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const WorkItem item = work_item(p.tiles, p.BH);
+  if (!item.valid) return;
+  const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int hist = p.hist_rows.v[b];
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
-  const int q0 = (blockIdx.x * kWaves + wave) * 32 * NQB;
+  const int q0 = (item.tile * kWaves + wave) * 32 * NQB;
   const int64_t bh = (int64_t)b * p.H + h;
 
   Wave w;
@@ -228,12 +230,15 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
 }
 
 // ---- dK, dV of the chunk's keys ---------------------------------------------------
-template <int D>
+// DV / DK select which of the two gradients this instantiation accumulates: computing both
+// in one wave needs more registers than two resident waves per SIMD have, so the kernel is
+// launched once per gradient (S is recomputed in both).
+template <int D, bool DV, bool DK>
 struct DkvWave {
   static constexpr int QSTEPS = D / 16;
   static constexpr int DB = D / 32;
-  bf16x8 kreg[QSTEPS], vreg[QSTEPS];  // B operands: K~ and V rows of this lane's chunk key
-  f32x16 dk[DB], dv[DB];
+  bf16x8 kreg[QSTEPS], vreg[DK ? QSTEPS : 1];  // B operands: K~ and V rows of this lane's chunk key
+  f32x16 dk[DK ? DB : 1], dv[DV ? DB : 1];
   OperandAddr<D> addr;
   int g;
   float scale_log2e;
@@ -245,7 +250,10 @@ struct DkvWave {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dk[db][r] = 0.f, dv[db][r] = 0.f;
+      for (int r = 0; r < 16; ++r) {
+        if (DK) dk[db][r] = 0.f;
+        if (DV) dv[db][r] = 0.f;
+      }
   }
 
   // One tile of 64 queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
@@ -254,51 +262,71 @@ struct DkvWave {
     for (int qb = 0; qb < KT / 32; ++qb) {
       // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      // phase order keeps few values live: S -> P -> dV products, then dP -> dS -> dK products
       f32x16 s, dp;
 #pragma unroll
       for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(qs, addr.row[st], qb), kreg[st], st == 0 ? zero : s);
-#pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
-      bf16x8 pb[2], dsb[2];
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 pb[2];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int r = 4 * rr + c;
-          const float pr = fast_exp2(fmaf(s[r], scale_log2e, -l4[c]));
-          const float ds = pr * (dp[r] - d4[c]);
-          pb[r >> 3][r & 7] = (__bf16)pr;
-          dsb[r >> 3][r & 7] = (__bf16)ds;
+          s[r] = fast_exp2(fmaf(s[r], scale_log2e, -l4[c]));  // P, kept in fp32 for dS
+          if (DV) pb[r >> 3][r & 7] = (__bf16)s[r];
         }
       }
-      // dV^T[d][key] += dO^T[d][q] P[q][key];  dK~^T[d][key] += Q~^T[d][q] dS[q][key]
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (DV) {
+        // dV^T[d][key] += dO^T[d][q] P[q][key]
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
+        for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
-          dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
+          for (int db = 0; db < DB; ++db) dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
+      }
+      if constexpr (DK) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 dsb[2];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int r = 4 * rr + c;
+            dsb[r >> 3][r & 7] = (__bf16)(s[r] * (dp[r] - d4[c]));
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
       }
     }
   }
 };
 
-template <int D, int OCC>
+template <int D, bool DV, bool DK, int OCC>
 __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p) {
-  using Wave = DkvWave<D>;
+  using Wave = DkvWave<D, DV, DK>;
   constexpr int TILE_BYTES = KT * D * 2;
   // Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [KT] and Delta [KT]
   __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES + 4 * KT * 4];
   float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const WorkItem item = work_item(p.tiles, p.BH);
+  if (!item.valid) return;
+  const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int64_t bh = (int64_t)b * p.H + h;
-  const int jc = (blockIdx.x * kWaves + wave) * 32 + i32;  // this lane's chunk key
+  const int jc = (item.tile * kWaves + wave) * 32 + i32;  // this lane's chunk key
   const bool live = jc < p.Nq;
   const int ntiles = (p.Nq + KT - 1) / KT;
 
@@ -315,7 +343,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
         y = *reinterpret_cast<const bf16x8*>(vrow + st * 16 + g * 8);
       }
       w.kreg[st] = x;
-      w.vreg[st] = y;
+      if (DK) w.vreg[st] = y;
     }
   }
 
@@ -367,11 +395,11 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
         f32x4 wk, wv;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          wk[c] = w.dk[db][4 * rr + c] * p.scale;
-          wv[c] = w.dv[db][4 * rr + c];
+          if (DK) wk[c] = w.dk[db][4 * rr + c] * p.scale;
+          if (DV) wv[c] = w.dv[db][4 * rr + c];
         }
-        *reinterpret_cast<f32x4*>(krow + 32 * db + 8 * rr + 4 * g) = wk;
-        *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
+        if (DK) *reinterpret_cast<f32x4*>(krow + 32 * db + 8 * rr + 4 * g) = wk;
+        if (DV) *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
       }
   }
 }
@@ -403,6 +431,8 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   p.dk_rot = dk_rot;
   p.dv = dv;
   p.H = g.H;
+  p.BH = g.B * g.H;
+  p.tiles = 0;
   p.Nq = op.Nq;
   p.cache_rows = (int64_t)g.C * g.T;
   p.scale = 1.0f / sqrtf((float)D);
@@ -417,16 +447,20 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
     ProfileScope prof("attn_bwd_dq_bf16", stream);
     if (bwd_variant() == 1) {
       const int qtile = kWaves * 32 * 2;
-      attn_bwd_dq_kernel<D, 2, 1><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+      p.tiles = (op.Nq + qtile - 1) / qtile;
+      attn_bwd_dq_kernel<D, 2, 1><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
     } else {
       const int qtile = kWaves * 32;
-      attn_bwd_dq_kernel<D, 1, 2><<<dim3((op.Nq + qtile - 1) / qtile, g.H, g.B), kThreads, 0, stream>>>(p);
+      p.tiles = (op.Nq + qtile - 1) / qtile;
+      attn_bwd_dq_kernel<D, 1, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
     }
   }
   const int ktile = kWaves * 32;
   {
     ProfileScope prof("attn_bwd_dkv_bf16", stream);
-    attn_bwd_dkv_kernel<D, 1><<<dim3((op.Nq + ktile - 1) / ktile, g.H, g.B), kThreads, 0, stream>>>(p);
+    p.tiles = (op.Nq + ktile - 1) / ktile;
+    attn_bwd_dkv_kernel<D, true, false, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+    attn_bwd_dkv_kernel<D, false, true, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
   }
   return hipGetLastError();
 }

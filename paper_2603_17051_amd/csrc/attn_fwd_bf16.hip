@@ -42,7 +42,7 @@ struct FwdParams {
   const __bf16* v_cache;
   __bf16* out;
   float* lse;
-  int H, Nq;
+  int H, Nq, BH, q_tiles;
   int64_t cache_rows;  // C*T
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -156,14 +156,16 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_fwd_bf16_kernel(FwdParams 
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char lds[kStages * STAGE_BYTES];
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const WorkItem item = work_item(p.q_tiles, p.BH);
+  if (!item.valid) return;
+  const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int hist = p.hist_rows.v[b];
   // key tiles: first the resident ring rows, then the chunk's rows, each with its own tail
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
-  const int q = (blockIdx.x * kWaves + wave) * 32 + i32;
+  const int q = (item.tile * kWaves + wave) * 32 + i32;
   const int64_t bh = (int64_t)b * p.H + h;
 
   Wave w;
@@ -270,7 +272,9 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   const int qtile = kWaves * 32;
-  dim3 grid((op.Nq + qtile - 1) / qtile, g.H, g.B);
+  p.BH = g.B * g.H;
+  p.q_tiles = (op.Nq + qtile - 1) / qtile;
+  dim3 grid(work_grid_size(p.q_tiles, p.BH));
   ProfileScope prof("attn_fwd_bf16", stream);
   attn_fwd_bf16_kernel<D, kStages, KPREF, OCC><<<grid, dim3(kThreads), 0, stream>>>(p);
   return hipGetLastError();
