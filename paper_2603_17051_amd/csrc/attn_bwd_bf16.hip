@@ -89,9 +89,11 @@ struct DqWave {
         for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
   }
 
-  // One 64-key tile.  Keys past the end of a segment need no masking here: their K rows
-  // are zero in LDS, so whatever dS they get contributes nothing to dQ~ = dS K~.
-  __device__ __forceinline__ void tile(const char* ks, const char* vs) {
+  // One 64-key tile of which the first `live` keys exist (wave-uniform).  Rows past the end
+  // of a segment are zero in LDS; their score is replaced so that P and dS are exactly 0
+  // (left alone, P = exp(0 - LSE) could overflow for a query whose logits are all very
+  // negative, and inf * 0 would poison dQ~ = dS K~).
+  __device__ __forceinline__ void tile(const char* ks, const char* vs, int live) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -101,6 +103,12 @@ struct DqWave {
         const bf16x8 ak = read_rows8<D>(ks, addr.row[st], kb);
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) s[qb] = mfma32(ak, qreg[qb][st], st == 0 ? zero : s[qb]);
+      }
+      if (live < 32 * (kb + 1)) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[qb][r] = 32 * kb + acc_row(r, g) >= live ? kNegBig : s[qb][r];
       }
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
@@ -206,7 +214,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   for (int t = 0; t < ntiles; ++t) {
     if (t + 1 < ntiles) issue(t + 1);
     const char* kbuf = lds + (t & 1) * 2 * TILE_BYTES;
-    w.tile(kbuf, kbuf + TILE_BYTES);
+    w.tile(kbuf, kbuf + TILE_BYTES, t < hist_tiles ? hist - t * KT : p.Nq - (t - hist_tiles) * KT);
     wait_vmem();
     __syncthreads();
   }

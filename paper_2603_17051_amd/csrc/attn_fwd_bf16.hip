@@ -2,8 +2,8 @@
 //
 // One workgroup = 4 wavefronts = 4 * 32 consecutive queries of one (stream, head).
 // The visible keys (resident ring rows, then the chunk's own rows) are walked in tiles of
-// 32; K and V tiles are streamed into a ring of 4 LDS stages by direct-to-LDS loads issued
-// three tiles ahead, one barrier per tile.  Everything is computed transposed so that
+// 32; K and V tiles are streamed into a ring of LDS stages by direct-to-LDS loads issued
+// two tiles ahead, one barrier per tile.  Everything is computed transposed so that
 // every lane owns ONE query:
 //   S^T[key][q] = K * Q~^T      (A = K tile from LDS, B = Q~ held in registers)
 //   O^T[d][q]  += V^T * P^T     (A = V tile through the transposing LDS read,
@@ -11,16 +11,19 @@
 // so the row maximum / sum of the softmax are in-lane reductions plus one exchange with
 // the partner lane l^32, and the rescale factor is a per-lane scalar.
 //
-// Because tile t+1 is already visible while tile t is processed, its K operands are read
-// into registers before the barrier and the MFMAs of the next tile start without an LDS
-// round trip.
+// Order inside a tile: the K operand reads are issued first, then the global->LDS loads
+// of the tile two ahead (their issue stalls while the memory pipeline is busy, which now
+// overlaps the LDS latency of the K reads), then the QK MFMAs, softmax, V reads and PV
+// MFMAs.  Runs of full tiles inside one key segment take a branch-free copy of the tile
+// code (no tail handling, no segment or end-of-loop tests); only the few tiles around the
+// segment boundaries take the general one.
 //
 // Softmax reference: probabilities are taken relative to a per-query reference M that is
-// only raised when a tile's maximum exceeds it by more than kRescaleSlack (in log2
-// units); fp32 accumulators and the bf16 exponent range make any smaller excess exact
-// enough, and the 64 accumulator multiplies of a rescale leave the common path.
+// only raised when a tile's probabilities relative to it sum to more than kSumLimit; fp32
+// accumulators and the bf16 exponent range make any smaller excess exact enough, and
+// both the row maximum and the 64 accumulator multiplies of a rescale leave the common path.
 // MFMA and vector-ALU work of one wave do not overlap on this hardware; the overlap
-// comes from two workgroups (two waves per SIMD) being resident per CU.
+// comes from three workgroups (three waves per SIMD) being resident per CU.
 #include <cstdlib>
 
 #include "kernels.hpp"
@@ -29,10 +32,8 @@
 namespace astro {
 namespace {
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 constexpr int KT = 32;                 // keys per LDS tile
-constexpr float kRescaleSlack = 40.f;  // log2 units: p <= 2^40 before the reference moves
+constexpr float kSumLimit = 0x1p44f;  // a lane's 16 probabilities may sum to this before the reference moves
 
 struct FwdParams {
   const __bf16* q_rot;
@@ -54,25 +55,23 @@ __device__ __forceinline__ float scale_in_place(float x, float a) {
   return x;
 }
 
-template <int D, bool KPREF>
+template <int D>
 struct FwdWave {
   static constexpr int QSTEPS = D / 16;  // MFMA k-steps of the QK product
   static constexpr int DB = D / 32;      // 32-row blocks of O^T
 
   bf16x8 qreg[QSTEPS];
-  bf16x8 kfrag[KPREF ? QSTEPS : 1];  // K operands of the tile about to be processed
   f32x16 o[DB];
-  float m_ref, l_run;  // reference (raw dot units), per-lane partial row sum
+  float mc, l_run;  // softmax reference in log2 units (scale*log2(e) * dot), per-lane partial row sum
   OperandAddr<D> addr;
   int g;
-  float scale_log2e, slack_raw;
+  float scale_log2e;
 
   __device__ __forceinline__ void init(int lane, float sl2e) {
     g = lane >> 5;
     scale_log2e = sl2e;
-    slack_raw = kRescaleSlack / sl2e;
     addr.init(lane);
-    m_ref = kNegBig;
+    mc = kNegBig;
     l_run = 0.f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -80,77 +79,97 @@ struct FwdWave {
       for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   }
 
-  __device__ __forceinline__ void load_kfrag(const char* ks) {
-#pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) kfrag[st] = read_rows8<D>(ks, addr.row[st], 0);
-  }
-
-  // One 32-key tile whose K operands are in kfrag; vs = its V tile, ks_next = K tile of the
-  // following one (already visible), read into kfrag for the next call.
-  // Rows of a tile past the end of its segment are zero in LDS: they add nothing to O
-  // (V = 0) but do add exp(0 - M) each to the row sum, which `dead_keys` (their number in
-  // this tile, wave-uniform) takes out again.
-  __device__ __forceinline__ void tile(const char* ks, const char* vs, const char* ks_next, bool has_next, int dead_keys) {
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 s;
-    if constexpr (KPREF) {
-#pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) s = mfma32(kfrag[st], qreg[st], st == 0 ? zero : s);
-      // next tile's K operands: their LDS latency hides under this tile's softmax and PV
-      if (has_next) load_kfrag(ks_next);
-    } else {
-#pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(ks, addr.row[st], 0), qreg[st], st == 0 ? zero : s);
-    }
-
-    float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-    mx = max_with_partner32(mx);
-    if (__builtin_expect(__any(mx > m_ref + slack_raw), 0)) {
-      const float m_new = fmaxf(m_ref, mx);
-      const float alpha = fast_exp2((m_ref - m_new) * scale_log2e);
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = scale_in_place(o[db][r], alpha);
-      m_ref = m_new;
-    }
-    const float mc = m_ref * scale_log2e;
-    bf16x8 pb[2];
+  // p = exp2(s * scale*log2(e) - mc) rounded to bf16, packed as the B operands of the PV
+  // product; returns this lane's part of the row sum, taken over the rounded values.
+  __device__ __forceinline__ float probabilities(const f32x16 s, bf16x8 (&pb)[2]) const {
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; r += 2) {
       const f32x2 e = {fast_exp2(fmaf(s[r], scale_log2e, -mc)), fast_exp2(fmaf(s[r + 1], scale_log2e, -mc))};
       const bf16x2 pk = __builtin_convertvector(e, bf16x2);
-      sum = add_pair(pk, sum);  // the row sum runs over the rounded values the PV product uses
+      sum = add_pair(pk, sum);
       pb[r >> 3][r & 7] = pk[0];
       pb[r >> 3][(r & 7) + 1] = pk[1];
     }
-    if (dead_keys > 0) {
-      // keys KT - dead_keys .. KT-1 of the tile are dead; this lane saw those among
-      // acc_row(r, g), each as exp2(0 - M) rounded to bf16
-      const float e0 = fast_exp2(-mc);
-      const f32x2 e = {e0, e0};
-      const bf16x2 pk = __builtin_convertvector(e, bf16x2);
-      int mine = 0;
+    return sum;
+  }
+
+  // A operands of the QK product: all 32 keys of the tile x D
+  __device__ __forceinline__ void read_k(const char* ks, bf16x8 (&kf)[QSTEPS]) const {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mine += (acc_row(r, g) >= KT - dead_keys) ? 1 : 0;
-      sum -= (float)mine * (float)pk[0];
+    for (int st = 0; st < QSTEPS; ++st) kf[st] = read_rows8<D>(ks, addr.row[st], 0);
+  }
+
+  // One 32-key tile: kf = its K operands, vs = its V rows in LDS; dead_keys (wave-uniform,
+  // only looked at when kTail) = number of rows at the tile's end that are past the segment.
+  // S^T tile of 32 keys x this wave's 32 queries from K operands in registers; with kTail,
+  // the dead_keys rows at the tile's end that lie past their segment (K and V rows zero in
+  // LDS) get a score that makes their probability exactly 0.
+  template <bool kTail>
+  __device__ __forceinline__ f32x16 scores(const bf16x8 (&kf)[QSTEPS], int dead_keys) const {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 s;
+#pragma unroll
+    for (int st = 0; st < QSTEPS; ++st) s = mfma32(kf[st], qreg[st], st == 0 ? zero : s);
+    if (kTail && dead_keys > 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = acc_row(r, g) >= KT - dead_keys ? kNegBig : s[r];
+    }
+    return s;
+  }
+
+  // One 32-key tile: kf = its K operands (read from ks), vs = its V rows in LDS; dead_keys
+  // is wave-uniform and only looked at when kTail.
+  template <bool kTail>
+  __device__ __forceinline__ void tile(const bf16x8 (&kf)[QSTEPS], const char* ks, const char* vs, int dead_keys) {
+    // Probabilities relative to the current reference.  No maximum is taken on the common
+    // path: a tile whose logits outgrow the reference shows up as a huge (or infinite) row
+    // sum; only then the scores are computed again (the first copy is gone: the exponentials
+    // are taken in place), the reference is raised and the probabilities are redone.
+    bf16x8 pb[2];
+    float sum = probabilities(scores<kTail>(kf, dead_keys), pb);
+    if (__builtin_expect(__any(!(sum <= kSumLimit)), 0)) {
+      bf16x8 kf2[QSTEPS];
+      read_k(ks, kf2);
+      const f32x16 s = scores<kTail>(kf2, dead_keys);
+      float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+      mx = max_with_partner32(mx);
+      const float mc_new = fmaxf(mc, mx * scale_log2e);
+      const float alpha = fast_exp2(mc - mc_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = scale_in_place(o[db][r], alpha);
+      mc = mc_new;
+      sum = probabilities(s, pb);
     }
     l_run += sum;
-    // O^T += V^T P^T (16 keys per MFMA k-step)
+    // O^T += V^T P^T (16 keys per MFMA k-step).  Only the operands of one k-step are in
+    // flight at a time: those of the second are read one by one behind the MFMAs of the
+    // first, into the registers these have just released.
+    bf16x8 v0[DB], v1[DB];
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
+    for (int db = 0; db < DB; ++db) v0[db] = read_cols8<D>(vs, addr.tr[db], 0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) o[db] = mfma32(read_cols8<D>(vs, addr.tr[db], 16 * s2), pb[s2], o[db]);
+    for (int db = 0; db < DB; ++db) {
+      o[db] = mfma32(v0[db], pb[0], o[db]);
+      v1[db] = read_cols8<D>(vs, addr.tr[db], 16);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // then two LDS reads
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o[db] = mfma32(v1[db], pb[1], o[db]);
   }
 };
 
-template <int D, int kStages, bool KPREF, int OCC>
-__global__ void __launch_bounds__(kThreads, OCC) attn_fwd_bf16_kernel(FwdParams p) {
-  using Wave = FwdWave<D, KPREF>;
+template <int D, int kStages, int kWaves, int OCC>
+__global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdParams p) {
+  using Wave = FwdWave<D>;
   constexpr int kAhead = kStages - 1;  // tiles in flight ahead of the one being processed
   constexpr int TILE_BYTES = KT * D * 2;
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, V tile
@@ -190,16 +209,19 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_fwd_bf16_kernel(FwdParams 
   ts.init();
   const uint32_t off_dense = ts.lane_offset(k_hist);    // stride D: ring K, ring V, rotated chunk K
   const uint32_t off_vchunk = ts.lane_offset(v_chunk);  // stride H*D
-  auto issue = [&](int t, char* stage) {
-    if (t < hist_tiles) {
-      ts.issue(k_hist, off_dense, t * KT, stage);
-      ts.issue(v_hist, off_dense, t * KT, stage + TILE_BYTES);
-    } else {
-      ts.issue(k_chunk, off_dense, (t - hist_tiles) * KT, stage);
-      ts.issue(v_chunk, off_vchunk, (t - hist_tiles) * KT, stage + TILE_BYTES);
-    }
+  auto issue_hist = [&](int t, char* stage) __attribute__((always_inline)) {
+    ts.issue(k_hist, off_dense, t * KT, stage);
+    ts.issue(v_hist, off_dense, t * KT, stage + TILE_BYTES);
   };
-  auto dead_in = [&](int t) {
+  auto issue = [&](int t, char* stage) __attribute__((always_inline)) {
+    const bool in_hist = t < hist_tiles;
+    const int row0 = (in_hist ? t : t - hist_tiles) * KT;
+    const RowSegment ks = in_hist ? k_hist : k_chunk;
+    const RowSegment vs = in_hist ? v_hist : v_chunk;
+    ts.issue(ks, off_dense, row0, stage);
+    ts.issue(vs, in_hist ? off_dense : off_vchunk, row0, stage + TILE_BYTES);
+  };
+  auto dead_in = [&](int t) __attribute__((always_inline)) {
     const int live = t < hist_tiles ? hist - t * KT : p.Nq - (t - hist_tiles) * KT;
     return live >= KT ? 0 : KT - live;
   };
@@ -215,27 +237,49 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_fwd_bf16_kernel(FwdParams 
   else
     wait_vmem();
   __syncthreads();
-  if constexpr (KPREF) w.load_kfrag(lds);
 
-  auto step = [&](int t, auto stage_c) {
+  // kGeneric: any tile.  kHist: tile t is a full tile of ring rows and tile t+kAhead is one
+  // too (possibly ragged), so nothing has to be tested: the bulk of a long window.
+  constexpr int kGeneric = 0, kHist = 1;
+  auto step = [&](int t, auto stage_c, auto mode_c) __attribute__((always_inline)) {
     constexpr int ST = decltype(stage_c)::value;
-    if (t + kAhead < ntiles) issue(t + kAhead, lds + ((ST + kAhead) % kStages) * STAGE_BYTES);
-    w.tile(lds + ST * STAGE_BYTES, lds + ST * STAGE_BYTES + TILE_BYTES, lds + ((ST + 1) % kStages) * STAGE_BYTES,
-           t + 1 < ntiles, dead_in(t));
+    constexpr int MODE = decltype(mode_c)::value;
+    char* stage = lds + ST * STAGE_BYTES;
+    char* refill = lds + ((ST + kAhead) % kStages) * STAGE_BYTES;
+    bf16x8 kf[Wave::QSTEPS];
+    w.read_k(stage, kf);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (MODE == kHist)
+      issue_hist(t + kAhead, refill);
+    else if (t + kAhead < ntiles)
+      issue(t + kAhead, refill);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (MODE == kGeneric)
+      w.template tile<true>(kf, stage, stage + TILE_BYTES, dead_in(t));
+    else
+      w.template tile<false>(kf, stage, stage + TILE_BYTES, 0);
+    // keep the next tile's K reads behind this tile's last MFMA: started earlier they
+    // would need registers that are not there
+    __builtin_amdgcn_sched_barrier(0);
     // tile t+1 .. t+kAhead-1 must have landed before the next tile starts; the newest may stay in flight
-    if (t + kAhead < ntiles && kAhead > 1)
+    if (kAhead > 1 && (MODE != kGeneric || t + kAhead < ntiles))
       wait_vmem_except<kLoadsPerTile>();
     else
       wait_vmem();
     __syncthreads();
   };
   // kStages tiles per trip so that every LDS stage is a compile-time offset
-  for (int t = 0; t < ntiles; t += kStages) {
-    step(t, std::integral_constant<int, 0>{});
-    if (kStages > 1 && t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1 % kStages>{});
-    if (kStages > 2 && t + 2 < ntiles) step(t + 2, std::integral_constant<int, 2 % kStages>{});
-    if (kStages > 3 && t + 3 < ntiles) step(t + 3, std::integral_constant<int, 3 % kStages>{});
-  }
+  auto group = [&](int t, auto mode_c) __attribute__((always_inline)) {
+    constexpr bool kAll = decltype(mode_c)::value != kGeneric;  // all kStages tiles exist
+    step(t, std::integral_constant<int, 0>{}, mode_c);
+    if (kStages > 1 && (kAll || t + 1 < ntiles)) step(t + 1, std::integral_constant<int, 1 % kStages>{}, mode_c);
+    if (kStages > 2 && (kAll || t + 2 < ntiles)) step(t + 2, std::integral_constant<int, 2 % kStages>{}, mode_c);
+    if (kStages > 3 && (kAll || t + 3 < ntiles)) step(t + 3, std::integral_constant<int, 3 % kStages>{}, mode_c);
+    static_assert(kStages <= 4, "unroll more steps");
+  };
+  int t = 0;
+  for (; t + kStages - 1 + kAhead < hist_tiles; t += kStages) group(t, std::integral_constant<int, kHist>{});
+  for (; t < ntiles; t += kStages) group(t, std::integral_constant<int, kGeneric>{});
 
   // ---- epilogue: normalise, write O [B, Nq, H, D] bf16 and LSE [B, H, Nq]
   const float l_tot = sum_with_partner32(w.l_run);
@@ -251,11 +295,11 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_fwd_bf16_kernel(FwdParams 
         for (int c = 0; c < 4; ++c) x[c] = (__bf16)(w.o[db][4 * rr + c] * inv);
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * rr + 4 * g) = x;
       }
-    if (g == 0) p.lse[bh * p.Nq + q] = w.m_ref * p.scale + __logf(l_tot);
+    if (g == 0) p.lse[bh * p.Nq + q] = w.mc * kLn2 + __logf(l_tot);
   }
 }
 
-template <int D, int kStages, bool KPREF, int OCC>
+template <int D, int kStages, int kWaves, int OCC>
 hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* lse, hipStream_t stream) {
   FwdParams p;
   p.q_rot = (const __bf16*)op.q_rot;
@@ -276,7 +320,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.q_tiles = (op.Nq + qtile - 1) / qtile;
   dim3 grid(work_grid_size(p.q_tiles, p.BH));
   ProfileScope prof("attn_fwd_bf16", stream);
-  attn_fwd_bf16_kernel<D, kStages, KPREF, OCC><<<grid, dim3(kThreads), 0, stream>>>(p);
+  attn_fwd_bf16_kernel<D, kStages, kWaves, OCC><<<grid, dim3(kWaves * 64), 0, stream>>>(p);
   return hipGetLastError();
 }
 
@@ -288,12 +332,9 @@ hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* 
     return e ? atoi(e) : 0;
   }();
   if (g.D == 128) {
-    if (variant == 1) return launch<128, 4, true, 2>(g, op, out, lse, stream);
-    if (variant == 2) return launch<128, 3, false, 2>(g, op, out, lse, stream);
-    if (variant == 3) return launch<128, 4, false, 2>(g, op, out, lse, stream);
-    return launch<128, 3, false, 3>(g, op, out, lse, stream);
+    return launch<128, 3, 4, 3>(g, op, out, lse, stream);
   }
-  return launch<64, 3, false, 3>(g, op, out, lse, stream);
+  return launch<64, 3, 4, 3>(g, op, out, lse, stream);
 }
 
 }  // namespace astro

@@ -153,12 +153,12 @@ struct TileStreamer {
     lane_chunk_bytes = ((lane % CPR) ^ swizzle<CPR>(lane_row)) * 16;
   }
   // per-lane byte offset of its row/chunk inside a tile of a source with this stride
-  __device__ __forceinline__ uint32_t lane_offset(const RowSegment& s) const {
+  __device__ __forceinline__ uint32_t lane_offset(const RowSegment s) const {
     return (uint32_t)lane_row * s.stride_bytes + (uint32_t)lane_chunk_bytes;
   }
   // Start copying rows [row0, row0 + TILE) of `s` into the LDS tile (asynchronous; complete
   // after s_waitcnt vmcnt(0) + barrier).  row0 must be wave-uniform.
-  __device__ __forceinline__ void issue(const RowSegment& s, uint32_t lane_off, int row0, char* lds_tile) const {
+  __device__ __forceinline__ void issue(const RowSegment s, uint32_t lane_off, int row0, char* lds_tile) const {
     typedef __attribute__((address_space(3))) void* lds_ptr;
 #pragma unroll
     for (int u = 0; u < kInsts; ++u) {

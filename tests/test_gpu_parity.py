@@ -138,6 +138,37 @@ def test_bf16_first_chunk_on_empty_cache_and_single_frame_appends():
     ls.close()
 
 
+def test_bf16_all_logits_strongly_negative_with_ragged_key_tiles():
+    """Every logit of every query is about -128, so exp(-LSE) is far beyond fp32 while the
+    softmax itself is ordinary; 45-token frames leave partly filled key tiles at the end of
+    the ring rows and of the chunk, whose padding must get probability exactly 0 (not
+    exp(0 - LSE) times a zero row).  Keys of mean -4 make dQ = dS K a cancellation of the
+    bf16-rounded dS against that mean, and inputs of magnitude 4 instead of 1 scale the rounding of dS into dK = dS^T Q: the
+    gradient gates are 4x the N(0,1) contract here (out and LSE keep it)."""
+    w = wl.Workload("bf16_neg", 14, 1, 2, 64, 5, 9, 3, 0, 1, 0, (0, 0, 0))
+    ls = Lockstep(w)
+    shape = (w.batch, w.n_q, w.heads, w.head_dim)
+    rep = []
+    for step in range(3):
+        noise = [wl.normal_f32(w.seed, t, shape, step) for t in (wl.T_Q, wl.T_K, wl.T_V, wl.T_DO)]
+        q = wl.f32_to_bf16_bits(4.0 + 0.5 * noise[0])
+        k = wl.f32_to_bf16_bits(-4.0 - 0.5 * noise[1])
+        v, do = wl.f32_to_bf16_bits(noise[2]), wl.f32_to_bf16_bits(noise[3])
+        out, lse = ls.fwd(q, k, v, 1)
+        ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), 1)
+        assert rl.max() < -100.0
+        assert_bf16_close(host_f64(out), ro, f"step {step} out", rep)
+        assert_bf16_close(host_f64(lse), rl, f"step {step} lse", rep)
+        dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), 1)
+        rq, rk, rv = ls.oracle.attn_bwd(ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), 1)
+        for got, ref, name in ((dq, rq, "dq"), (dk, rk, "dk"), (dv, rv, "dv")):
+            assert np.isfinite(host_f64(got)).all(), name
+            assert_bf16_close(host_f64(got), ref, f"step {step} {name}", rep, rms_gate=4e-2, abs_tol=8e-2)
+        ls.append(k, v, 1)
+    _report(rep[-5:])
+    ls.close()
+
+
 def test_bad_calls_on_a_device_cache_are_rejected_before_launch():
     import torch
     import paper_2603_17051_amd as A
