@@ -61,6 +61,7 @@ def main() -> int:
     ap.add_argument("--workload", default="rl_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-calibration", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (streams and heads shard "
@@ -140,8 +141,17 @@ def main() -> int:
     dominant = max((n for n in ktimes if kernel_flops(n, w)), key=lambda n: ktimes[n][1])
     d_avg = ktimes[dominant][1] / ktimes[dominant][0]
     achieved = kernel_flops(dominant, w) / (d_avg * 1e-3) / 1e12
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 counter runs of this workload
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_rl_bwd.json")) as f:
+            ent = json.load(f)["kernels"].get(dominant) if args.workload == "rl_bwd" else None
+        if ent:
+            traffic = ent["fetch_bytes"] + ent["write_bytes"]
+    except (OSError, ValueError, KeyError):
+        pass
     roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(d_avg, 4)}
 
     result = {
@@ -198,6 +208,30 @@ def main() -> int:
             ce.close()
             del qe, ke, ve, oe, le, wse
         result["extras"] = extras
+
+    # ---- what the chip sustains on MFMAs alone and on a plain copy (context for the peaks) -----
+    if not args.no_calibration:
+        wgs, iters = 512, 4000
+        sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+        calib = {}
+        for label, ops in (("normal", dev_bf16(wl.normal_bf16(wl.BASE_SEED, 99, (8 * 256 * 8,)))),
+                           ("zeros", torch.zeros(8 * 256 * 8, dtype=torch.bfloat16, device=dev))):
+            A.astro_calib_mfma(ops, wgs, iters, sink)
+            A.astro_profile_begin()
+            for _ in range(3):
+                A.astro_calib_mfma(ops, wgs, iters, sink)
+            la, tot = A.astro_profile_end()["calib_mfma_bf16"]
+            calib[f"mfma_only_tflops_{label}_operands"] = round(wgs * 4 * iters * 16 * 32768.0 / (tot / la * 1e-3) / 1e12, 1)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        A.astro_calib_copy(src, dst)
+        A.astro_profile_begin()
+        for _ in range(5):
+            A.astro_calib_copy(src, dst)
+        la, tot = A.astro_profile_end()["calib_copy"]
+        calib["copy_gbs_read_plus_write"] = round(2.0 * (1 << 30) / (tot / la * 1e-3) / 1e9, 1)
+        result["calibration"] = calib
+        del src, dst, sink
 
     # ---- the fp64 oracle on the host cores, bounded sample of the same workload -----
     if not args.no_cpu_baseline:

@@ -152,6 +152,19 @@ typedef struct astro_kernel_time {
 int astro_profile_begin(void);
 int astro_profile_end(astro_kernel_time_t *out, int32_t max_entries, int32_t *n_entries);
 
+/* Machine calibration for the roofline the attention kernels are priced against (no
+ * operation of the paper; both are timed through astro_profile_* under the names
+ * "calib_mfma_bf16" and "calib_copy").
+ * astro_calib_mfma: `workgroups` workgroups of 4 waves issue nothing but bf16 32x32x16
+ *   MFMAs: iters * 16 per wave, 32768 flop each.  operands: device, 8 * 256 * 16 bytes of
+ *   bf16 (4 A and 4 B fragments per lane); the clock the chip sustains depends on their
+ *   values (all zero vs N(0,1)).  sink: device, workgroups * 256 floats, overwritten.
+ *   workgroups in 1 .. 65536, iters in 1 .. 2^20.
+ * astro_calib_copy: dst[0 .. bytes) = src[0 .. bytes), device pointers, 16-byte aligned,
+ *   bytes a multiple of 16; moves 2 * bytes through HBM when bytes exceeds the caches. */
+int astro_calib_mfma(const void *operands, int32_t workgroups, int32_t iters, float *sink, void *hip_stream);
+int astro_calib_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 /* Static, never-NULL description of an error code. */
 const char *astro_strerror(int err);
 

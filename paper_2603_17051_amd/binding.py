@@ -30,7 +30,7 @@ EXPORTED = (
     "astro_kvcache_bytes", "astro_kvcache_create", "astro_kvcache_destroy", "astro_kvcache_reset",
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
-    "astro_profile_begin", "astro_profile_end",
+    "astro_profile_begin", "astro_profile_end", "astro_calib_mfma", "astro_calib_copy",
 )
 
 
@@ -76,6 +76,8 @@ def _load() -> ctypes.CDLL:
                                          c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.astro_profile_begin.argtypes = []
     lib.astro_profile_end.argtypes = [P(astro_kernel_time_t), c_int32, P(c_int32)]
+    lib.astro_calib_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+    lib.astro_calib_copy.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     for name in EXPORTED:
         getattr(lib, name).restype = c_int
     lib.astro_strerror.argtypes = [c_int]
@@ -270,3 +272,19 @@ def astro_profile_end(max_entries: int = 32):
     n = c_int32(0)
     _check(_lib.astro_profile_end(buf, max_entries, byref(n)), "astro_profile_end")
     return {buf[i].name.decode(): (buf[i].launches, float(buf[i].total_ms)) for i in range(n.value)}
+
+
+def astro_calib_mfma(operands: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> None:
+    """Launch the MFMA-only calibration kernel (timed via astro_profile_* as "calib_mfma_bf16")."""
+    if operands.numel() * operands.element_size() < 8 * 256 * 16 or sink.numel() < workgroups * 256:
+        raise ValueError("operand or sink buffer too small")
+    _check(_lib.astro_calib_mfma(_ptr(operands), int(workgroups), int(iters), _ptr(sink), _stream(stream)),
+           "astro_calib_mfma")
+
+
+def astro_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """Launch the streaming-copy calibration kernel (timed as "calib_copy")."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst smaller than src")
+    _check(_lib.astro_calib_copy(_ptr(src), _ptr(dst), c_size_t(nbytes), _stream(stream)), "astro_calib_copy")

@@ -155,7 +155,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   constexpr int TILE_BYTES = KT * D * 2;
   __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
 
-  const WorkItem item = work_item(p.tiles, p.BH);
+  const WorkItem item = work_item(p.tiles, p.BH, true);
   if (!item.valid) return;
   const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -328,7 +328,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES + 4 * KT * 4];
   float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
 
-  const WorkItem item = work_item(p.tiles, p.BH);
+  const WorkItem item = work_item(p.tiles, p.BH, false);
   if (!item.valid) return;
   const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

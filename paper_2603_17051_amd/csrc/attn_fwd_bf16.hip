@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char lds[kStages * STAGE_BYTES];
 
-  const WorkItem item = work_item(p.q_tiles, p.BH);
+  const WorkItem item = work_item(p.q_tiles, p.BH, true);
   if (!item.valid) return;
   const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

@@ -1,0 +1,74 @@
+// Machine calibration for the roofline context: what this GPU sustains on nothing but bf16
+// MFMAs (with the operand values the caller supplies: the sustained clock depends on them)
+// and on a plain streaming copy.  Timed like every other launch, through astro_profile_*.
+#include "kernels.hpp"
+#include "mfma_common.hpp"
+
+namespace astro {
+namespace {
+
+constexpr int kOperandSets = 4;
+
+// Each wave keeps 4 A and 4 B operand fragments in registers and issues independent
+// 32x32x16 MFMAs into 4 accumulators, pairing the fragments differently each time so that
+// the multiplier inputs change between consecutive instructions as they do in a real tile loop.
+__global__ void __launch_bounds__(256, 2) calib_mfma_kernel(const bf16x8* __restrict__ operands, float* __restrict__ sink,
+                                                            int iters) {
+  bf16x8 a[kOperandSets], b[kOperandSets];
+#pragma unroll
+  for (int j = 0; j < kOperandSets; ++j) {
+    a[j] = operands[(2 * j) * 256 + threadIdx.x];
+    b[j] = operands[(2 * j + 1) * 256 + threadIdx.x];
+  }
+  f32x16 c[kOperandSets];
+#pragma unroll
+  for (int j = 0; j < kOperandSets; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c[j][r] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int u = 0; u < kOperandSets; ++u)
+#pragma unroll
+      for (int j = 0; j < kOperandSets; ++j) c[j] = mfma32(a[(j + u) % kOperandSets], b[j], c[j]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < kOperandSets; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += c[j][r];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ void __launch_bounds__(256) calib_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+}  // namespace astro
+
+using namespace astro;
+
+extern "C" {
+
+int astro_calib_mfma(const void* operands, int32_t workgroups, int32_t iters, float* sink, void* hip_stream) {
+  if (!operands || !sink || workgroups <= 0 || workgroups > (1 << 16) || iters <= 0 || iters > (1 << 20)) return ASTRO_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  {
+    ProfileScope prof("calib_mfma_bf16", stream);
+    calib_mfma_kernel<<<dim3(workgroups), dim3(256), 0, stream>>>(static_cast<const bf16x8*>(operands), sink, iters);
+  }
+  return hipGetLastError() == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
+}
+
+int astro_calib_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16 != 0) return ASTRO_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  {
+    ProfileScope prof("calib_copy", stream);
+    calib_copy_kernel<<<dim3(256 * 16), dim3(256), 0, stream>>>(static_cast<const f32x4*>(src), static_cast<f32x4*>(dst), bytes / 16);
+  }
+  return hipGetLastError() == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
+}
+
+}  // extern "C"

@@ -313,3 +313,23 @@ def test_bf16_rl_backward_sampled_pairs():
         assert_bf16_close(host_f64(dv[b, :, h]), rv[b, :, h], f"stream {b} head {h} dv", rep)
     _report(rep)
     ls.close()
+
+
+def test_calibration_kernels_compute_what_their_rates_assume():
+    """The rates bench.py derives from the calibration launches assume iters * 16 MFMAs of
+    32x32x16 per wave and a full copy: all-ones operands make every accumulator entry
+    iters * 4 * 16, and the copy must reproduce its source."""
+    import torch
+    import paper_2603_17051_amd as A
+    ones = torch.ones(8 * 256 * 8, dtype=torch.bfloat16, device="cuda:0")
+    sink = torch.zeros(3 * 256, dtype=torch.float32, device="cuda:0")
+    A.astro_calib_mfma(ones, 3, 5, sink)
+    torch.cuda.synchronize()
+    assert (sink == 64.0 * 5 * 4 * 16).all()
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    A.astro_calib_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(A.AstroError):
+        A.astro_calib_mfma(ones, 0, 5, sink)
