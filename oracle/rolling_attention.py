@@ -302,3 +302,65 @@ class RollingCacheOracle:
         if return_dscores or history_grads:
             return dq, dk, dv, extra
         return dq, dk, dv
+
+    # -- group-wise candidates over one shared, frozen context (Sec. 3.2) ------------------
+    # Clip-level group sampling: G candidate continuations of stream b are generated from the
+    # SAME rolling cache; candidate g's chunk attends to the stream's visible history and to
+    # its own chunk only, never to another candidate's.  Tensors are [B*G, Nq, H, D] with
+    # candidate c = b*G + g.  By definition this is attention of each candidate against its
+    # stream's context, so it is written as exactly that loop.
+    def _candidate_pairs(self, group: int, candidates, heads):
+        cs = range(self.B * group) if candidates is None else candidates
+        hs = range(self.H) if heads is None else heads
+        return [(c, h) for c in cs for h in hs]
+
+    def group_attn_fwd(self, q, k_chunk, v_chunk, n_frames: int, group: int, candidates=None, heads=None):
+        """O [B*G,Nq,H,D], LSE [B*G,H,Nq]; unlisted (candidate, head) pairs stay NaN."""
+        Nq = n_frames * self.T
+        assert group >= 1
+        assert q.shape == k_chunk.shape == v_chunk.shape == (self.B * group, Nq, self.H, self.D)
+        out = np.full((self.B * group, Nq, self.H, self.D), np.nan)
+        lse = np.full((self.B * group, self.H, Nq), np.nan)
+        context = {}
+        for c, h in self._candidate_pairs(group, candidates, heads):
+            b = c // group
+            if (b, h) not in context:
+                context[(b, h)] = self._context(b, h)
+            kh, vh = context[(b, h)]
+            phi = self._chunk_phi(b, n_frames)
+            qt = rope_rotate(np.asarray(q[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
+            kc = rope_rotate(np.asarray(k_chunk[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
+            kt = np.concatenate([kh, kc], 0)
+            vv = np.concatenate([vh, np.asarray(v_chunk[c, :, h, :], dtype=np.float64)], 0)
+            _, o, l = _softmax_attention(qt, kt, vv)
+            out[c, :, h, :] = o
+            lse[c, h, :] = l
+        return out, lse
+
+    def group_attn_bwd(self, q, k_chunk, v_chunk, dout, n_frames: int, group: int, candidates=None, heads=None):
+        """dQ, dK_chunk, dV_chunk [B*G,Nq,H,D]; the shared context is a constant (Sec. 3.3)."""
+        Nq = n_frames * self.T
+        scale = 1.0 / np.sqrt(np.float64(self.D))
+        shape = (self.B * group, Nq, self.H, self.D)
+        assert q.shape == k_chunk.shape == v_chunk.shape == dout.shape == shape
+        dq, dk, dv = (np.full(shape, np.nan) for _ in range(3))
+        context = {}
+        for c, h in self._candidate_pairs(group, candidates, heads):
+            b = c // group
+            if (b, h) not in context:
+                context[(b, h)] = self._context(b, h)
+            kh, vh = context[(b, h)]
+            nh = kh.shape[0]
+            phi = self._chunk_phi(b, n_frames)
+            qt = rope_rotate(np.asarray(q[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
+            kc = rope_rotate(np.asarray(k_chunk[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
+            kt = np.concatenate([kh, kc], 0)
+            vv = np.concatenate([vh, np.asarray(v_chunk[c, :, h, :], dtype=np.float64)], 0)
+            do = np.asarray(dout[c, :, h, :], dtype=np.float64)
+            p, o, _ = _softmax_attention(qt, kt, vv)
+            delta = (do * o).sum(axis=1, keepdims=True)
+            ds = p * (do @ vv.T - delta)
+            dq[c, :, h, :] = rope_rotate((scale * (ds @ kt))[:, None, :], -phi)[:, 0]
+            dk[c, :, h, :] = rope_rotate((scale * (ds[:, nh:].T @ qt))[:, None, :], -phi)[:, 0]
+            dv[c, :, h, :] = p[:, nh:].T @ do
+        return dq, dk, dv
