@@ -139,6 +139,27 @@ int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_ch
                          float *dv_chunk, void *workspace, size_t workspace_bytes,
                          void *hip_stream);
 
+/* Group-wise candidates over one shared, frozen cache (Sec. 3.2, clip-level group
+ * sampling: G candidate continuations are generated from the same rolling KV cache and
+ * compared; Sec. 3.3 for the backward).  The chunk tensors hold `group` candidate chunks
+ * per cache stream: q, k_chunk, v_chunk, out, dout, dq, dk_chunk, dv_chunk are
+ * [B*group, n_frames*T, H, D] and lse is [B*group, H, n_frames*T], candidate
+ * c = b*group + g.  Every candidate of stream b sits at the chunk position of stream b
+ * (frames start_frame + next_n ...), attends to stream b's resident frames and to its OWN
+ * chunk keys only, never to another candidate's.  Otherwise exactly as the chunk calls
+ * (which are these with group = 1): same dtypes, workspace rules, errors; the cache is not
+ * modified (append the chosen candidate's k_chunk, v_chunk afterwards).
+ * group >= 1 and B*group <= ASTRO_MAX_BATCH, else ASTRO_ERR_INVALID_ARG. */
+int astro_group_attn_workspace_bytes(const astro_kvcache_t *cache, int32_t n_frames, int32_t group,
+                                     size_t *fwd_bytes, size_t *bwd_bytes);
+int astro_group_attn_fwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
+                         const void *v_chunk, int32_t n_frames, int32_t group, void *out,
+                         float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
+int astro_group_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
+                         const void *v_chunk, const void *out, const float *lse, const void *dout,
+                         int32_t n_frames, int32_t group, float *dq, float *dk_chunk,
+                         float *dv_chunk, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid (Sec. 3.2 / 3.3 name no kernels; this times the library's own):
  * between begin and end every kernel launch is bracketed by HIP events recorded on
  * the stream it is launched on.  end() waits for those events (host-synchronous),

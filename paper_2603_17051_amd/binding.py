@@ -30,6 +30,7 @@ EXPORTED = (
     "astro_kvcache_bytes", "astro_kvcache_create", "astro_kvcache_destroy", "astro_kvcache_reset",
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
+    "astro_group_attn_workspace_bytes", "astro_group_attn_fwd", "astro_group_attn_bwd",
     "astro_profile_begin", "astro_profile_end", "astro_calib_mfma", "astro_calib_copy",
 )
 
@@ -74,6 +75,11 @@ def _load() -> ctypes.CDLL:
                                          c_void_p, c_size_t, c_void_p]
     lib.astro_chunk_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.astro_group_attn_workspace_bytes.argtypes = [c_void_p, c_int32, c_int32, P(c_size_t), P(c_size_t)]
+    lib.astro_group_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
+                                         c_void_p, c_size_t, c_void_p]
+    lib.astro_group_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.astro_profile_begin.argtypes = []
     lib.astro_profile_end.argtypes = [P(astro_kernel_time_t), c_int32, P(c_int32)]
     lib.astro_calib_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
@@ -186,9 +192,9 @@ def astro_kvcache_reset(cache: KVCache, stream_index: int = -1, start_frame: int
     _check(_lib.astro_kvcache_reset(cache.handle, stream_index, start_frame), "astro_kvcache_reset")
 
 
-def _check_chunk_tensor(cache: KVCache, t: torch.Tensor, n_frames: int, name: str, dtype=None) -> None:
+def _check_chunk_tensor(cache: KVCache, t: torch.Tensor, n_frames: int, name: str, dtype=None, group: int = 1) -> None:
     d = cache.desc
-    shape = (d.batch, n_frames * cache.tokens_per_frame, d.heads, d.head_dim)
+    shape = (d.batch * group, n_frames * cache.tokens_per_frame, d.heads, d.head_dim)
     if tuple(t.shape) != shape or not t.is_contiguous() or t.dtype != (dtype or cache.torch_dtype):
         raise ValueError(f"{name}: expected contiguous {dtype or cache.torch_dtype} tensor of shape {shape}, "
                          f"got {t.dtype} {tuple(t.shape)}")
@@ -212,6 +218,58 @@ def astro_kvcache_tables(cache: KVCache):
     _check(_lib.astro_kvcache_tables(cache.handle, sf, sp, nn), "astro_kvcache_tables")
     rows = lambda a: [list(a[b * C:(b + 1) * C]) for b in range(B)]
     return rows(sf), rows(sp), list(nn)
+
+
+def astro_group_attn_workspace_bytes(cache: KVCache, n_frames: int, group: int):
+    f, b = c_size_t(0), c_size_t(0)
+    _check(_lib.astro_group_attn_workspace_bytes(cache.handle, n_frames, group, byref(f), byref(b)),
+           "astro_group_attn_workspace_bytes")
+    return f.value, b.value
+
+
+def astro_group_attn_fwd(cache: KVCache, q, k_chunk, v_chunk, n_frames: int, group: int, out=None, lse=None,
+                         workspace=None, stream=None):
+    """`group` candidate chunks per cache stream, tensors [B*group, Nq, H, D].
+    Returns (out [B*group, Nq, H, D], lse [B*group, H, Nq] fp32)."""
+    for name, t in (("q", q), ("k_chunk", k_chunk), ("v_chunk", v_chunk)):
+        _check_chunk_tensor(cache, t, n_frames, name, group=group)
+    d = cache.desc
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((d.batch * group, d.heads, q.shape[1]), dtype=torch.float32, device=q.device)
+    _check_chunk_tensor(cache, out, n_frames, "out", group=group)
+    if lse.dtype != torch.float32 or not lse.is_contiguous() or lse.numel() != d.batch * group * d.heads * q.shape[1]:
+        raise ValueError("lse: expected contiguous fp32 [B*group, H, Nq]")
+    if workspace is None:
+        workspace = cache.workspace(astro_group_attn_workspace_bytes(cache, n_frames, group)[0], q.device)
+    _check(_lib.astro_group_attn_fwd(cache.handle, _ptr(q), _ptr(k_chunk), _ptr(v_chunk), n_frames, group, _ptr(out),
+                                     _ptr(lse), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "astro_group_attn_fwd")
+    return out, lse
+
+
+def astro_group_attn_bwd(cache: KVCache, q, k_chunk, v_chunk, out, lse, dout, n_frames: int, group: int,
+                         dq=None, dk_chunk=None, dv_chunk=None, workspace=None, stream=None):
+    """Returns fp32 (dq, dk_chunk, dv_chunk), each [B*group, Nq, H, D]."""
+    for name, t in (("q", q), ("k_chunk", k_chunk), ("v_chunk", v_chunk), ("out", out), ("dout", dout)):
+        _check_chunk_tensor(cache, t, n_frames, name, group=group)
+    mk = lambda: torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dq = mk() if dq is None else dq
+    dk_chunk = mk() if dk_chunk is None else dk_chunk
+    dv_chunk = mk() if dv_chunk is None else dv_chunk
+    for name, t in (("dq", dq), ("dk_chunk", dk_chunk), ("dv_chunk", dv_chunk)):
+        _check_chunk_tensor(cache, t, n_frames, name, torch.float32, group=group)
+    d = cache.desc
+    if lse.dtype != torch.float32 or not lse.is_contiguous() or lse.numel() != d.batch * group * d.heads * q.shape[1]:
+        raise ValueError("lse: expected contiguous fp32 [B*group, H, Nq]")
+    if workspace is None:
+        workspace = cache.workspace(astro_group_attn_workspace_bytes(cache, n_frames, group)[1], q.device)
+    _check(_lib.astro_group_attn_bwd(cache.handle, _ptr(q), _ptr(k_chunk), _ptr(v_chunk), _ptr(out), _ptr(lse),
+                                     _ptr(dout), n_frames, group, _ptr(dq), _ptr(dk_chunk), _ptr(dv_chunk),
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "astro_group_attn_bwd")
+    return dq, dk_chunk, dv_chunk
 
 
 def astro_chunk_attn_workspace_bytes(cache: KVCache, n_frames: int):

@@ -30,10 +30,12 @@ namespace {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-DevGeom dev_geom(const astro_kvcache* c) {
+// group > 1: the chunk tensors hold `group` candidates per cache stream; the kernels then see
+// B * group streams of chunk data
+DevGeom dev_geom(const astro_kvcache* c, int group = 1) {
   const RingGeometry& g = c->geo;
   DevGeom d;
-  d.B = g.B; d.H = g.H; d.D = g.D; d.gh = g.gh; d.gw = g.gw; d.T = g.T; d.C = g.C; d.S = g.S;
+  d.B = g.B * group; d.H = g.H; d.D = g.D; d.gh = g.gh; d.gw = g.gw; d.T = g.T; d.C = g.C; d.S = g.S;
   d.n_t = g.n_t; d.n_h = g.n_h; d.n_w = g.n_w;
   d.inv_freq_t = c->d_inv_freq_t;
   d.tab_h = c->d_tab_h;
@@ -45,12 +47,12 @@ struct Workspace {
   size_t q_rot, kc_rot, dq_rot, dk_rot, scratch, total;
 };
 
-Workspace carve(const astro_kvcache* c, int n_frames, bool bwd) {
+Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group) {
   const RingGeometry& g = c->geo;
   const size_t nq = (size_t)n_frames * g.T;
-  const size_t rot = align256((size_t)g.B * g.H * nq * g.D * g.elem_bytes());
-  const size_t grad = align256((size_t)g.B * g.H * nq * g.D * sizeof(float));
-  const DevGeom d = dev_geom(c);
+  const size_t rot = align256((size_t)g.B * group * g.H * nq * g.D * g.elem_bytes());
+  const size_t grad = align256((size_t)g.B * group * g.H * nq * g.D * sizeof(float));
+  const DevGeom d = dev_geom(c, group);
   Workspace w{};
   size_t off = 0;
   w.q_rot = off; off += rot;
@@ -68,10 +70,17 @@ Workspace carve(const astro_kvcache* c, int n_frames, bool bwd) {
   return w;
 }
 
-int check_chunk_call(const astro_kvcache* c, int n_frames) {
+int check_group(const astro_kvcache* c, int group) {
+  if (!c) return ASTRO_ERR_INVALID_ARG;
+  if (group < 1 || (int64_t)c->geo.B * group > ASTRO_MAX_BATCH) return ASTRO_ERR_INVALID_ARG;
+  return ASTRO_OK;
+}
+
+int check_chunk_call(const astro_kvcache* c, int n_frames, int group) {
   if (!c) return ASTRO_ERR_INVALID_ARG;
   if (c->geo.host_only) return ASTRO_ERR_BAD_STATE;
   if (n_frames < 1 || n_frames > c->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
+  if (check_group(c, group) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
   if (!c->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
   // the kernels address one stream's chunk tensor and one head's ring with 32-bit byte offsets
   const RingGeometry& g = c->geo;
@@ -81,16 +90,20 @@ int check_chunk_call(const astro_kvcache* c, int n_frames) {
   return ASTRO_OK;
 }
 
-void stream_ints(const astro_kvcache* c, StreamInts* first_frame, StreamInts* next_n, StreamInts* hist_rows) {
-  for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
+// first_frame / next_n are indexed by candidate (cache stream * group + g), hist_rows by cache stream
+void stream_ints(const astro_kvcache* c, StreamInts* first_frame, StreamInts* next_n, StreamInts* hist_rows,
+                 int group = 1) {
+  for (int i = 0; i < ASTRO_MAX_BATCH; ++i) {
+    const int b = i / group;
     const bool live = b < c->geo.B;
-    if (first_frame) first_frame->v[b] = live ? c->tables.start(b) + c->tables.next_n(b) : 0;
-    if (next_n) next_n->v[b] = live ? c->tables.next_n(b) : 0;
-    if (hist_rows) hist_rows->v[b] = live ? c->tables.resident(b) * c->geo.T : 0;
+    if (first_frame) first_frame->v[i] = live ? c->tables.start(b) + c->tables.next_n(b) : 0;
+    if (next_n) next_n->v[i] = live ? c->tables.next_n(b) : 0;
+    if (hist_rows) hist_rows->v[i] = i < c->geo.B ? c->tables.resident(i) * c->geo.T : 0;
   }
 }
 
-AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w, const void* v_chunk, int n_frames) {
+AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w, const void* v_chunk, int n_frames,
+                           int group) {
   AttnOperands op;
   op.q_rot = ws + w.q_rot;
   op.kc_rot = ws + w.kc_rot;
@@ -98,17 +111,18 @@ AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w,
   op.k_cache = c->k_storage;
   op.v_cache = c->v_storage;
   op.Nq = n_frames * c->geo.T;
+  op.group = group;
   stream_ints(c, nullptr, nullptr, &op.hist_rows);
   return op;
 }
 
 // rotate Q and K_chunk into the workspace (head-major)
 hipError_t stage_chunk(const astro_kvcache* c, const void* q, const void* k_chunk, char* ws, const Workspace& w,
-                       int n_frames, hipStream_t stream) {
+                       int n_frames, int group, hipStream_t stream) {
   StreamInts first, next;
-  stream_ints(c, &first, &next, nullptr);
+  stream_ints(c, &first, &next, nullptr, group);
   ScatterDst dst{ws + w.q_rot, ws + w.kc_rot, (int64_t)n_frames * c->geo.T, 0};
-  return launch_rope_scatter(dev_geom(c), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next, stream);
+  return launch_rope_scatter(dev_geom(c, group), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next, stream);
 }
 
 }  // namespace
@@ -214,28 +228,29 @@ int astro_kvcache_tables(const astro_kvcache_t* cache, int32_t* slot_frame, int3
   return ASTRO_OK;
 }
 
-int astro_chunk_attn_workspace_bytes(const astro_kvcache_t* cache, int32_t n_frames, size_t* fwd_bytes,
+int astro_group_attn_workspace_bytes(const astro_kvcache_t* cache, int32_t n_frames, int32_t group, size_t* fwd_bytes,
                                      size_t* bwd_bytes) {
   if (!cache) return ASTRO_ERR_INVALID_ARG;
   if (n_frames < 1 || n_frames > cache->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
-  if (fwd_bytes) *fwd_bytes = carve(cache, n_frames, false).total;
-  if (bwd_bytes) *bwd_bytes = carve(cache, n_frames, true).total;
+  if (check_group(cache, group) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
+  if (fwd_bytes) *fwd_bytes = carve(cache, n_frames, false, group).total;
+  if (bwd_bytes) *bwd_bytes = carve(cache, n_frames, true, group).total;
   return ASTRO_OK;
 }
 
-int astro_chunk_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
-                         int32_t n_frames, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                         void* hip_stream) {
-  const int rc = check_chunk_call(cache, n_frames);
+int astro_group_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         int32_t n_frames, int32_t group, void* out, float* lse, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_chunk_call(cache, n_frames, group);
   if (rc != ASTRO_OK) return rc;
   if (!q || !k_chunk || !v_chunk || !out || !lse) return ASTRO_ERR_INVALID_ARG;
-  const Workspace w = carve(cache, n_frames, false);
+  const Workspace w = carve(cache, n_frames, false, group);
   if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return ASTRO_ERR_WORKSPACE;
   char* ws = (char*)workspace;
   hipStream_t stream = (hipStream_t)hip_stream;
-  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, stream) != hipSuccess) return ASTRO_ERR_HIP;
-  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames);
-  const DevGeom d = dev_geom(cache);
+  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, group, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames, group);
+  const DevGeom d = dev_geom(cache, group);
   hipError_t e;
   if (cache->geo.dtype == ASTRO_F32)
     e = launch_attn_fwd_f32(d, op, (float*)out, lse, (float*)(ws + w.scratch), stream);
@@ -244,19 +259,20 @@ int astro_chunk_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_ch
   return e == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
 }
 
-int astro_chunk_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
-                         const void* out, const float* lse, const void* dout, int32_t n_frames, float* dq,
-                         float* dk_chunk, float* dv_chunk, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  const int rc = check_chunk_call(cache, n_frames);
+int astro_group_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         const void* out, const float* lse, const void* dout, int32_t n_frames, int32_t group,
+                         float* dq, float* dk_chunk, float* dv_chunk, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  const int rc = check_chunk_call(cache, n_frames, group);
   if (rc != ASTRO_OK) return rc;
   if (!q || !k_chunk || !v_chunk || !out || !lse || !dout || !dq || !dk_chunk || !dv_chunk) return ASTRO_ERR_INVALID_ARG;
-  const Workspace w = carve(cache, n_frames, true);
+  const Workspace w = carve(cache, n_frames, true, group);
   if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return ASTRO_ERR_WORKSPACE;
   char* ws = (char*)workspace;
   hipStream_t stream = (hipStream_t)hip_stream;
-  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, stream) != hipSuccess) return ASTRO_ERR_HIP;
-  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames);
-  const DevGeom d = dev_geom(cache);
+  if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, group, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames, group);
+  const DevGeom d = dev_geom(cache, group);
   float* dq_rot = (float*)(ws + w.dq_rot);
   float* dk_rot = (float*)(ws + w.dk_rot);
   hipError_t e;
@@ -268,10 +284,28 @@ int astro_chunk_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_ch
   if (e != hipSuccess) return ASTRO_ERR_HIP;
   // gradients w.r.t. the un-rotated Q and K_chunk: inverse rotation, back to token-major
   StreamInts first;
-  stream_ints(cache, &first, nullptr, nullptr);
+  stream_ints(cache, &first, nullptr, nullptr, group);
   if (launch_rope_unscatter_f32(d, dq_rot, dq, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
   if (launch_rope_unscatter_f32(d, dk_rot, dk_chunk, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
   return ASTRO_OK;
+}
+
+int astro_chunk_attn_workspace_bytes(const astro_kvcache_t* cache, int32_t n_frames, size_t* fwd_bytes,
+                                     size_t* bwd_bytes) {
+  return astro_group_attn_workspace_bytes(cache, n_frames, 1, fwd_bytes, bwd_bytes);
+}
+
+int astro_chunk_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         int32_t n_frames, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  return astro_group_attn_fwd(cache, q, k_chunk, v_chunk, n_frames, 1, out, lse, workspace, workspace_bytes, hip_stream);
+}
+
+int astro_chunk_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                         const void* out, const float* lse, const void* dout, int32_t n_frames, float* dq,
+                         float* dk_chunk, float* dv_chunk, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return astro_group_attn_bwd(cache, q, k_chunk, v_chunk, out, lse, dout, n_frames, 1, dq, dk_chunk, dv_chunk, workspace,
+                              workspace_bytes, hip_stream);
 }
 
 const char* astro_strerror(int err) {

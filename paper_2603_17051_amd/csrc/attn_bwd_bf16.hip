@@ -36,7 +36,8 @@ struct BwdParams {
   float* dq_rot;  // [B][H][Nq][D]
   float* dk_rot;  // [B][H][Nq][D]
   float* dv;      // [B, Nq, H, D]
-  int H, Nq, BH, tiles;  // tiles = workgroups per (stream, head) of the kernel being launched
+  int H, Nq, BH, tiles;  // BH = candidates * heads; tiles = workgroups per pair of the kernel being launched
+  int group;             // candidates per cache stream
   int64_t cache_rows;
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -157,10 +158,11 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
 
   const WorkItem item = work_item(p.tiles, p.BH, true);
   if (!item.valid) return;
-  const int b = item.bh / p.H, h = item.bh % p.H;
+  const PairIndex pair = split_pair(item.bh, p.H, p.group);
+  const int b = pair.b, h = pair.h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
-  const int hist = p.hist_rows.v[b];
+  const int hist = p.hist_rows.v[pair.cache_b];
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
   const int q0 = (item.tile * kWaves + wave) * 32 * NQB;
@@ -189,8 +191,8 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
     w.delta[qb] = live ? p.delta[bh * p.Nq + q] : 0.f;
   }
 
-  const RowSegment k_hist = make_segment(p.k_cache + bh * p.cache_rows * D, D, hist, D);
-  const RowSegment v_hist = make_segment(p.v_cache + bh * p.cache_rows * D, D, hist, D);
+  const RowSegment k_hist = make_segment(p.k_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
+  const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
   TileStreamer<D, KT, kWaves> ts;
@@ -446,6 +448,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   p.scale = 1.0f / sqrtf((float)D);
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
+  p.group = op.group;
   const int64_t n_rows = (int64_t)g.B * op.Nq * g.H;
   {
     ProfileScope prof("attn_bwd_delta", stream);

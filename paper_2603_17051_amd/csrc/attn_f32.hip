@@ -13,20 +13,22 @@ struct F32Operands {
   const float* v_chunk;
   const float* k_cache;
   const float* v_cache;
-  int H, D, Nq, nk_stride;
+  int H, D, Nq, nk_stride, group;
   int64_t cache_rows;
   float scale;
   StreamInts hist_rows;
 };
 
 __device__ __forceinline__ const float* key_row(const F32Operands& p, int b, int h, int j) {
-  const int hist = p.hist_rows.v[b];
-  if (j < hist) return p.k_cache + (((int64_t)b * p.H + h) * p.cache_rows + j) * p.D;
+  const int cb = b / p.group;  // cache stream of candidate b
+  const int hist = p.hist_rows.v[cb];
+  if (j < hist) return p.k_cache + (((int64_t)cb * p.H + h) * p.cache_rows + j) * p.D;
   return p.kc_rot + (((int64_t)b * p.H + h) * p.Nq + (j - hist)) * p.D;
 }
 __device__ __forceinline__ const float* value_row(const F32Operands& p, int b, int h, int j) {
-  const int hist = p.hist_rows.v[b];
-  if (j < hist) return p.v_cache + (((int64_t)b * p.H + h) * p.cache_rows + j) * p.D;
+  const int cb = b / p.group;
+  const int hist = p.hist_rows.v[cb];
+  if (j < hist) return p.v_cache + (((int64_t)cb * p.H + h) * p.cache_rows + j) * p.D;
   return p.v_chunk + (((int64_t)b * p.Nq + (j - hist)) * p.H + h) * p.D;
 }
 __device__ __forceinline__ float* score_row(float* s, const F32Operands& p, int bh, int q) {
@@ -50,7 +52,7 @@ __device__ float block_reduce(float x, bool is_max, float* red) {
 __global__ void scores_kernel(F32Operands p, float* s) {
   const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H, q = blockIdx.y;
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   if (j >= nk) return;
   const float* qr = p.q_rot + ((int64_t)bh * p.Nq + q) * p.D;
   const float* kr = key_row(p, b, h, j);
@@ -63,7 +65,7 @@ __global__ void scores_kernel(F32Operands p, float* s) {
 __global__ void softmax_kernel(F32Operands p, float* s, float* lse) {
   __shared__ float red[256];
   const int bh = blockIdx.y, b = bh / p.H, q = blockIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   float* row = score_row(s, p, bh, q);
   float m = -3.0e38f;
   for (int j = threadIdx.x; j < nk; j += blockDim.x) m = fmaxf(m, row[j]);
@@ -79,7 +81,7 @@ __global__ void softmax_kernel(F32Operands p, float* s, float* lse) {
 // O[q][d] = sum_j P[q][j] V[j][d]; grid (Nq, B*H), D threads
 __global__ void pv_kernel(F32Operands p, const float* s, float* out) {
   const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H, q = blockIdx.x, d = threadIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   const float* row = s + ((int64_t)bh * p.Nq + q) * p.nk_stride;
   float acc = 0.f;
   for (int j = 0; j < nk; ++j) acc = fmaf(row[j], value_row(p, b, h, j)[d], acc);
@@ -92,7 +94,7 @@ __global__ void probs_delta_kernel(F32Operands p, float* s, const float* lse, co
                                    float* delta) {
   __shared__ float red[256];
   const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H, q = blockIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   float* row = score_row(s, p, bh, q);
   const float l = lse[(int64_t)bh * p.Nq + q];
   for (int j = threadIdx.x; j < nk; j += blockDim.x) row[j] = expf(row[j] - l);
@@ -107,7 +109,7 @@ __global__ void probs_delta_kernel(F32Operands p, float* s, const float* lse, co
 __global__ void dscores_kernel(F32Operands p, const float* prob, const float* dout, const float* delta, float* ds) {
   const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H, q = blockIdx.y;
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   if (j >= nk) return;
   const float* dor = dout + (((int64_t)b * p.Nq + q) * p.H + h) * p.D;
   const float* vr = value_row(p, b, h, j);
@@ -120,7 +122,7 @@ __global__ void dscores_kernel(F32Operands p, const float* prob, const float* do
 // dQ~[q][d] = scale * sum_j dS[q][j] K~[j][d]; grid (Nq, B*H), D threads; head-major out
 __global__ void dq_kernel(F32Operands p, const float* ds, float* dq_rot) {
   const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H, q = blockIdx.x, d = threadIdx.x;
-  const int nk = p.hist_rows.v[b] + p.Nq;
+  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
   const float* row = ds + ((int64_t)bh * p.Nq + q) * p.nk_stride;
   float acc = 0.f;
   for (int j = 0; j < nk; ++j) acc = fmaf(row[j], key_row(p, b, h, j)[d], acc);
@@ -132,7 +134,7 @@ __global__ void dq_kernel(F32Operands p, const float* ds, float* dq_rot) {
 __global__ void dkv_kernel(F32Operands p, const float* prob, const float* ds, const float* dout, float* dk_rot,
                            float* dv) {
   const int bh = blockIdx.y, b = bh / p.H, h = bh % p.H, jc = blockIdx.x, d = threadIdx.x;
-  const int j = p.hist_rows.v[b] + jc;
+  const int j = p.hist_rows.v[b / p.group] + jc;
   float ak = 0.f, av = 0.f;
   for (int q = 0; q < p.Nq; ++q) {
     const int64_t o = ((int64_t)bh * p.Nq + q) * p.nk_stride + j;
@@ -156,6 +158,7 @@ F32Operands make_operands(const DevGeom& g, const AttnOperands& op) {
   p.nk_stride = g.C * g.T + op.Nq;
   p.cache_rows = (int64_t)g.C * g.T;
   p.scale = (float)(1.0 / sqrt((double)g.D));
+  p.group = op.group;
   p.hist_rows = op.hist_rows;
   return p;
 }

@@ -43,7 +43,7 @@ struct FwdParams {
   const __bf16* v_cache;
   __bf16* out;
   float* lse;
-  int H, Nq, BH, q_tiles;
+  int H, Nq, BH, q_tiles, group;  // BH = candidates * heads; group = candidates per cache stream
   int64_t cache_rows;  // C*T
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -177,10 +177,11 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
 
   const WorkItem item = work_item(p.q_tiles, p.BH, true);
   if (!item.valid) return;
-  const int b = item.bh / p.H, h = item.bh % p.H;
+  const PairIndex pair = split_pair(item.bh, p.H, p.group);
+  const int b = pair.b, h = pair.h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
-  const int hist = p.hist_rows.v[b];
+  const int hist = p.hist_rows.v[pair.cache_b];
   // key tiles: first the resident ring rows, then the chunk's rows, each with its own tail
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
@@ -200,8 +201,8 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     }
   }
 
-  const RowSegment k_hist = make_segment(p.k_cache + bh * p.cache_rows * D, D, hist, D);
-  const RowSegment v_hist = make_segment(p.v_cache + bh * p.cache_rows * D, D, hist, D);
+  const RowSegment k_hist = make_segment(p.k_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
+  const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
   using Streamer = TileStreamer<D, KT, kWaves>;
@@ -315,6 +316,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.scale = 1.0f / sqrtf((float)D);
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
+  p.group = op.group;
   const int qtile = kWaves * 32;
   p.BH = g.B * g.H;
   p.q_tiles = (op.Nq + qtile - 1) / qtile;

@@ -61,7 +61,9 @@ hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* 
                                      const StreamInts& first_frame, hipStream_t stream);
 
 // Keys / values visible to a chunk: the resident ring rows (a prefix of the ring) and
-// the chunk's own rows.
+// the chunk's own rows.  With group > 1 the chunk tensors hold `group` candidate chunks per
+// cache stream (candidate c = b*group + g, DevGeom::B counts candidates); all candidates of
+// stream b see that stream's ring rows and only their own chunk rows.
 struct AttnOperands {
   const void* q_rot;    // [B][H][Nq][D] rotated queries (workspace)
   const void* kc_rot;   // [B][H][Nq][D] rotated chunk keys (workspace)
@@ -69,7 +71,8 @@ struct AttnOperands {
   const void* k_cache;  // [B][H][C*T][D]
   const void* v_cache;  // [B][H][C*T][D]
   int Nq;
-  StreamInts hist_rows;  // resident ring rows per stream
+  int group;             // candidates per cache stream (1 = plain chunk attention)
+  StreamInts hist_rows;  // resident ring rows per CACHE stream
 };
 
 // ---- fp32 debug path -------------------------------------------------------

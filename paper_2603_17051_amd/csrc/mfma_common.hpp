@@ -198,6 +198,25 @@ __device__ __forceinline__ WorkItem work_item(int tiles_per_head, int BH, bool b
   return w;
 }
 
+// A work item's pair index -> candidate, head and cache stream.  Pairs are ordered (cache
+// stream, head, candidate), so the `group` candidates that share one head's ring rows are
+// neighbours (same XCD under the contiguous split, same time otherwise).
+struct PairIndex {
+  int b;         // candidate = stream of the chunk tensors: cache stream * group + g
+  int h;         // head
+  int cache_b;   // cache stream
+  int cache_bh;  // cache stream * H + head
+};
+__device__ __forceinline__ PairIndex split_pair(int pair, int H, int group) {
+  PairIndex x;
+  const int g = pair % group;
+  x.cache_bh = pair / group;
+  x.cache_b = x.cache_bh / H;
+  x.h = x.cache_bh - x.cache_b * H;
+  x.b = x.cache_b * group + g;
+  return x;
+}
+
 // wait until this wave's outstanding global loads (including direct-to-LDS ones) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 // ... all but the N most recently issued ones (loads complete in issue order)

@@ -113,6 +113,22 @@ def test_workspace_sizes_are_reported():
     c.close()
 
 
+def test_group_workspace_scales_with_the_group_and_bad_groups_are_rejected():
+    c = A.astro_kvcache_create(host_only=True, **GOOD)
+    f1, b1 = A.astro_chunk_attn_workspace_bytes(c, 2)
+    assert A.astro_group_attn_workspace_bytes(c, 2, 1) == (f1, b1)
+    f4, b4 = A.astro_group_attn_workspace_bytes(c, 2, 4)
+    assert f4 == 4 * f1 and b4 >= 4 * (b1 - 1024)
+    for bad in (0, -1, binding.ASTRO_MAX_BATCH + 1):
+        with pytest.raises(A.AstroError) as e:
+            A.astro_group_attn_workspace_bytes(c, 2, bad)
+        assert e.value.code == binding.ASTRO_ERR_INVALID_ARG
+    # a host-only handle refuses the compute call itself
+    lib = binding.library()
+    assert lib.astro_group_attn_fwd(c.handle, None, None, None, 2, 2, None, None, None, 0, None) == binding.ASTRO_ERR_BAD_STATE
+    c.close()
+
+
 @pytest.mark.parametrize("C,S,Fc,start", [(1, 0, 1, 0), (4, 0, 1, 0), (4, 1, 3, 7), (12, 1, 3, 0), (18, 0, 3, 41),
                                           (21, 3, 3, 0), (5, 4, 1, 2), (7, 2, 5, 1000), (256, 3, 11, 5)])
 def test_tables_follow_the_naive_ring_simulation(C, S, Fc, start):

@@ -82,8 +82,10 @@ PROD_FWD = Workload("prod_fwd", 2, 1, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21
 GROUP_FWD_APPEND = Workload("group_fwd_append", 3, 8, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21))
 STREAM_EVICT = Workload("stream_evict", 4, 1, 12, 128, 30, 52, 12, 1, 3, 0, (22, 21, 21))
 RL_BWD = Workload("rl_bwd", 5, 4, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21))
+# one stream whose frozen cache is shared by a group of candidate chunks (group size given at the call)
+SHARED_PREFIX = Workload("shared_prefix", 6, 1, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21))
 
-WORKLOADS = {w.name: w for w in (TINY_FWD, PROD_FWD, GROUP_FWD_APPEND, STREAM_EVICT, RL_BWD)}
+WORKLOADS = {w.name: w for w in (TINY_FWD, PROD_FWD, GROUP_FWD_APPEND, STREAM_EVICT, RL_BWD, SHARED_PREFIX)}
 
 
 # ----------------------------------------------------------------------------
@@ -145,6 +147,14 @@ def chunk_inputs(w: Workload, step: int = 0, with_dout: bool = False):
     if with_dout:
         return q, k, v, normal_bf16(w.seed, T_DO, shape, step)
     return q, k, v
+
+
+def group_inputs(w: Workload, group: int, step: int = 0, with_dout: bool = False):
+    """As chunk_inputs, for `group` candidate chunks per stream: [B*group, Fc*T, H, D],
+    candidate c = b*group + g."""
+    shape = (w.batch * group, w.n_q, w.heads, w.head_dim)
+    ids = (T_Q, T_K, T_V, T_DO) if with_dout else (T_Q, T_K, T_V)
+    return tuple(normal_bf16(w.seed + 1000 * group, t, shape, step) for t in ids)
 
 
 def history_frame_pool(w: Workload, n_pool: int):
