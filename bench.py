@@ -207,6 +207,39 @@ def main() -> int:
             extras[name] = ent
             ce.close()
             del qe, ke, ve, oe, le, wse
+        # group-wise candidates over one shared, frozen cache (8 candidate chunks, one stream)
+        we, G = wl.WORKLOADS["shared_prefix"], 8
+        ce = make_cache(we)
+        qe, ke, ve, de = (dev_bf16(x) for x in wl.group_inputs(we, G, with_dout=True))
+        oe = torch.empty_like(qe)
+        le = torch.empty((we.batch * G, we.heads, we.n_q), dtype=torch.float32, device=dev)
+        gq, gk, gv = (torch.empty(qe.shape, dtype=torch.float32, device=dev) for _ in range(3))
+        wse = torch.empty(max(A.astro_group_attn_workspace_bytes(ce, we.chunk_frames, G)), dtype=torch.uint8, device=dev)
+
+        def group_step():
+            A.astro_group_attn_fwd(ce, qe, ke, ve, we.chunk_frames, G, oe, le, wse)
+            A.astro_group_attn_bwd(ce, qe, ke, ve, oe, le, de, we.chunk_frames, G, gq, gk, gv, wse)
+
+        for _ in range(2):
+            group_step()
+        torch.cuda.synchronize()
+        n = 10
+        t0 = time.perf_counter()
+        for _ in range(n):
+            group_step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / n
+        fl = G * (flops_fwd(we) + flops_bwd(we))
+        A.astro_profile_begin()
+        group_step()
+        kt = A.astro_profile_end()
+        fwd_ms = kt["attn_fwd_bf16"][1] / kt["attn_fwd_bf16"][0]
+        extras["shared_prefix_group8"] = {
+            "fwd_bwd_ms": round(ms, 4), "fwd_bwd_tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+            "frac_bf16_mfma_peak": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+            "fwd_kernel_ms": round(fwd_ms, 4), "fwd_kernel_tflops": round(G * flops_fwd(we) / (fwd_ms * 1e-3) / 1e12, 1)}
+        ce.close()
+        del qe, ke, ve, de, oe, le, gq, gk, gv, wse
         result["extras"] = extras
 
     # ---- what the chip sustains on MFMAs alone and on a plain copy (context for the peaks) -----
