@@ -7,3 +7,4 @@ from .rolling_attention import (  # noqa: F401
     round_to_bf16,
     visible_history,
 )
+from .nft_loss import nft_loss, normalized_reward  # noqa: F401,E402
