@@ -240,6 +240,25 @@ def main() -> int:
             "fwd_kernel_ms": round(fwd_ms, 4), "fwd_kernel_tflops": round(G * flops_fwd(we) / (fwd_ms * 1e-3) / 1e12, 1)}
         ce.close()
         del qe, ke, ve, de, oe, le, gq, gk, gv, wse
+        # fused clip-level loss: 24 (one group) and 192 candidate clips of 3 latent frames 16 x 60 x 104, bf16
+        for n_clips in (24, 192):
+            shape = (n_clips, 3 * 16 * 60 * 104)
+            vs = [torch.randn(shape, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(4)]
+            adv = torch.randn(n_clips, device=dev)
+            msk = (torch.arange(n_clips, device=dev) % 5 == 0).to(torch.int32)
+            l3 = torch.empty(3, device=dev)
+            gr = torch.empty(shape, dtype=torch.float32, device=dev)
+            wsn = torch.empty(A.astro_nft_loss_workspace_bytes(*shape), dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                A.astro_nft_loss(*vs, adv, msk, 1.0, 1.0, 0.1, l3, gr, wsn)
+            A.astro_profile_begin()
+            for _ in range(20):
+                A.astro_nft_loss(*vs, adv, msk, 1.0, 1.0, 0.1, l3, gr, wsn)
+            la, tot = A.astro_profile_end()["nft_loss"]
+            nbytes = shape[0] * shape[1] * (4 * 2 + 4)  # four bf16 tensors read, fp32 gradient written
+            extras[f"nft_loss_{n_clips}_clips"] = {"ms": round(tot / la, 4), "gbs": round(nbytes / (tot / la * 1e-3) / 1e9, 1),
+                                                  "frac_hbm_peak": round(nbytes / (tot / la * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            del vs, gr, wsn
         result["extras"] = extras
 
     # ---- what the chip sustains on MFMAs alone and on a plain copy (context for the peaks) -----

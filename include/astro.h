@@ -160,6 +160,28 @@ int astro_group_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_ch
                          int32_t n_frames, int32_t group, float *dq, float *dk_chunk,
                          float *dv_chunk, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Clip-level forward-process RL loss and its gradient (Sec. 3.1 eq. (1)-(2); Sec. 3.3 reward
+ * normalisation; Sec. 3.4 selective KL; Alg. 1, Phase 2), one fused pass.  For sample i of
+ * n_samples, each of elems_per_sample elements:
+ *   r~_i = clip(A_i / a_max, -1, 1) / 2 + 0.5
+ *   v+ = (1 - beta) v_old + beta v_theta,   v- = (1 + beta) v_old - beta v_theta
+ *   L_policy = (1/n) sum_i [ r~_i |v+ - target|^2 + (1 - r~_i) |v- - target|^2 ]   (|.|^2 = sum over the sample)
+ *   L_KL     = (1/|M|) sum_{i : kl_mask_i != 0} |v_theta - v_ref|^2               (0 if no sample is masked)
+ *   loss[0] = L_policy + lambda_kl L_KL, loss[1] = L_policy, loss[2] = L_KL
+ *   grad_v_theta = d loss[0] / d v_theta (fp32, same shape).
+ * v_theta, v_old, v_ref, target: device, [n_samples, elems_per_sample] of `dtype` (ASTRO_BF16
+ * or ASTRO_F32), 16-byte aligned; elems_per_sample a multiple of 8 (bf16) / 4 (fp32), else
+ * ASTRO_ERR_UNSUPPORTED.  advantage: device fp32 [n_samples]; kl_mask: device int32
+ * [n_samples]; loss: device fp32 [3]; grad_v_theta: device fp32, 16-byte aligned.
+ * n_samples in 1 .. 65535; a_max > 0.  workspace: device, >= the reported bytes, 256-byte
+ * aligned.  Arithmetic in fp32, the final sums in fp64; results do not depend on timing. */
+int astro_nft_loss_workspace_bytes(int32_t n_samples, int64_t elems_per_sample, size_t *bytes);
+int astro_nft_loss(const void *v_theta, const void *v_old, const void *v_ref, const void *target,
+                   const float *advantage, const int32_t *kl_mask, int32_t n_samples,
+                   int64_t elems_per_sample, int32_t dtype, float a_max, float beta, float lambda_kl,
+                   float *loss, float *grad_v_theta, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
+
 /* Measurement aid (Sec. 3.2 / 3.3 name no kernels; this times the library's own):
  * between begin and end every kernel launch is bracketed by HIP events recorded on
  * the stream it is launched on.  end() waits for those events (host-synchronous),

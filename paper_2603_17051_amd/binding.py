@@ -31,6 +31,7 @@ EXPORTED = (
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
     "astro_group_attn_workspace_bytes", "astro_group_attn_fwd", "astro_group_attn_bwd",
+    "astro_nft_loss_workspace_bytes", "astro_nft_loss",
     "astro_profile_begin", "astro_profile_end", "astro_calib_mfma", "astro_calib_copy",
 )
 
@@ -80,6 +81,9 @@ def _load() -> ctypes.CDLL:
                                          c_void_p, c_size_t, c_void_p]
     lib.astro_group_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.astro_nft_loss_workspace_bytes.argtypes = [c_int32, ctypes.c_int64, P(c_size_t)]
+    lib.astro_nft_loss.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, ctypes.c_int64,
+                                   c_int32, c_float, c_float, c_float, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.astro_profile_begin.argtypes = []
     lib.astro_profile_end.argtypes = [P(astro_kernel_time_t), c_int32, P(c_int32)]
     lib.astro_calib_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
@@ -346,3 +350,39 @@ def astro_calib_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     if dst.numel() * dst.element_size() < nbytes:
         raise ValueError("dst smaller than src")
     _check(_lib.astro_calib_copy(_ptr(src), _ptr(dst), c_size_t(nbytes), _stream(stream)), "astro_calib_copy")
+
+
+def astro_nft_loss_workspace_bytes(n_samples: int, elems_per_sample: int) -> int:
+    b = c_size_t(0)
+    _check(_lib.astro_nft_loss_workspace_bytes(int(n_samples), int(elems_per_sample), byref(b)),
+           "astro_nft_loss_workspace_bytes")
+    return b.value
+
+
+def astro_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, a_max: float, beta: float, lambda_kl: float,
+                   loss=None, grad=None, workspace=None, stream=None):
+    """Fused clip-level loss: tensors [n, ...] (bf16 or fp32, contiguous), advantage fp32 [n],
+    kl_mask int32 [n].  Returns (loss [3] fp32 = total, policy, kl; grad fp32 like v_theta)."""
+    n = v_theta.shape[0]
+    elems = v_theta.numel() // n
+    for name, t in (("v_old", v_old), ("v_ref", v_ref), ("target", target)):
+        if t.shape != v_theta.shape or t.dtype != v_theta.dtype or not t.is_contiguous():
+            raise ValueError(f"{name}: must match v_theta in shape and dtype and be contiguous")
+    if v_theta.dtype not in (torch.bfloat16, torch.float32) or not v_theta.is_contiguous():
+        raise ValueError("v_theta: expected contiguous bf16 or fp32")
+    if advantage.dtype != torch.float32 or advantage.numel() != n or kl_mask.dtype != torch.int32 or kl_mask.numel() != n:
+        raise ValueError("advantage: fp32 [n]; kl_mask: int32 [n]")
+    dev = v_theta.device
+    loss = torch.empty(3, dtype=torch.float32, device=dev) if loss is None else loss
+    grad = torch.empty(v_theta.shape, dtype=torch.float32, device=dev) if grad is None else grad
+    if grad.dtype != torch.float32 or grad.numel() != v_theta.numel() or loss.dtype != torch.float32 or loss.numel() < 3:
+        raise ValueError("grad: fp32 like v_theta; loss: fp32 [3]")
+    need = astro_nft_loss_workspace_bytes(n, elems)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    dtype = ASTRO_BF16 if v_theta.dtype == torch.bfloat16 else ASTRO_F32
+    _check(_lib.astro_nft_loss(_ptr(v_theta), _ptr(v_old), _ptr(v_ref), _ptr(target), _ptr(advantage), _ptr(kl_mask),
+                               n, elems, dtype, float(a_max), float(beta), float(lambda_kl), _ptr(loss), _ptr(grad),
+                               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "astro_nft_loss")
+    return loss, grad

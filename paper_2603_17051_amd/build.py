@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libastro.so")
-SOURCES = ["astro_api.hip", "rope_scatter.hip", "attn_f32.hip", "attn_fwd_bf16.hip", "attn_bwd_bf16.hip", "profile.hip", "calib.hip"]
+SOURCES = ["astro_api.hip", "rope_scatter.hip", "attn_f32.hip", "attn_fwd_bf16.hip", "attn_bwd_bf16.hip", "profile.hip", "calib.hip", "nft_loss.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-unused-value",
     # no NaN / infinity is ever produced on purpose (masks use large finite values), so
