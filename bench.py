@@ -240,6 +240,35 @@ def main() -> int:
             "fwd_kernel_ms": round(fwd_ms, 4), "fwd_kernel_tflops": round(G * flops_fwd(we) / (fwd_ms * 1e-3) / 1e12, 1)}
         ce.close()
         del qe, ke, ve, de, oe, le, gq, gk, gv, wse
+        # backward with and without the detach (the paper's "Clip + Full BP" comparison point), config-5 shape
+        we = wl.WORKLOADS["rl_bwd"]
+        ce = make_cache(we)
+        qe, ke, ve, de = (dev_bf16(x) for x in wl.chunk_inputs(we, with_dout=True))
+        oe, le = A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames)
+        g3 = [torch.empty(qe.shape, dtype=torch.float32, device=dev) for _ in range(3)]
+        ring_shape = (we.batch, we.capacity_frames * we.tokens_per_frame, we.heads, we.head_dim)
+        gk, gv = (torch.zeros(ring_shape, dtype=torch.float32, device=dev) for _ in range(2))
+        wsf = torch.empty(A.astro_chunk_attn_bwd_full_workspace_bytes(ce, we.chunk_frames), dtype=torch.uint8, device=dev)
+        times = {}
+        for label, fn in (("detached", lambda: A.astro_chunk_attn_bwd(ce, qe, ke, ve, oe, le, de, we.chunk_frames, *g3, wsf)),
+                          ("full", lambda: A.astro_chunk_attn_bwd_full(ce, qe, ke, ve, oe, le, de, we.chunk_frames, *g3, gk, gv, wsf))):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            times[label] = (time.perf_counter() - t0) * 1e3 / 10
+        full_flops = 10.0 * we.n_q * we.n_k * we.head_dim * we.heads * we.batch  # all five products over all keys
+        extras["backward_detached_vs_full"] = {
+            "detached_ms": round(times["detached"], 4), "full_ms": round(times["full"], 4),
+            "detached_tflops": round(flops_bwd(we) / (times["detached"] * 1e-3) / 1e12, 1),
+            "full_tflops": round(full_flops / (times["full"] * 1e-3) / 1e12, 1),
+            "full_over_detached_time": round(times["full"] / times["detached"], 3),
+            "extra_gradient_bytes": int(2 * np.prod(ring_shape) * 4)}
+        ce.close()
+        del qe, ke, ve, de, oe, le, g3, gk, gv, wsf
         # fused clip-level loss: 24 (one group) and 192 candidate clips of 3 latent frames 16 x 60 x 104, bf16
         for n_clips in (24, 192):
             shape = (n_clips, 3 * 16 * 60 * 104)

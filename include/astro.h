@@ -139,6 +139,20 @@ int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_ch
                          float *dv_chunk, void *workspace, size_t workspace_bytes,
                          void *hip_stream);
 
+/* The non-detached backward ("Clip + Full BP" of the paper's streaming-training ablation,
+ * Sec. 4.5, Table 4(a)): everything astro_chunk_attn_bwd writes, plus the gradients the detach drops,
+ *   dk_cache, dv_cache: device fp32 [B, C*T, H, D], row = slot*T + token, w.r.t. the keys
+ *   (UN-rotated, as they were appended) and values of the frames resident in the ring.
+ * Rows of slots that hold no frame are not written.  bf16 caches only (ASTRO_ERR_UNSUPPORTED
+ * for ASTRO_F32).  workspace: >= astro_chunk_attn_bwd_full_workspace_bytes, 256-byte aligned. */
+int astro_chunk_attn_bwd_full_workspace_bytes(const astro_kvcache_t *cache, int32_t n_frames,
+                                              size_t *bytes);
+int astro_chunk_attn_bwd_full(astro_kvcache_t *cache, const void *q, const void *k_chunk,
+                              const void *v_chunk, const void *out, const float *lse,
+                              const void *dout, int32_t n_frames, float *dq, float *dk_chunk,
+                              float *dv_chunk, float *dk_cache, float *dv_cache, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
+
 /* Group-wise candidates over one shared, frozen cache (Sec. 3.2, clip-level group
  * sampling: G candidate continuations are generated from the same rolling KV cache and
  * compared; Sec. 3.3 for the backward).  The chunk tensors hold `group` candidate chunks

@@ -32,6 +32,7 @@ EXPORTED = (
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
     "astro_group_attn_workspace_bytes", "astro_group_attn_fwd", "astro_group_attn_bwd",
     "astro_nft_loss_workspace_bytes", "astro_nft_loss",
+    "astro_chunk_attn_bwd_full_workspace_bytes", "astro_chunk_attn_bwd_full",
     "astro_profile_begin", "astro_profile_end", "astro_calib_mfma", "astro_calib_copy",
 )
 
@@ -84,6 +85,10 @@ def _load() -> ctypes.CDLL:
     lib.astro_nft_loss_workspace_bytes.argtypes = [c_int32, ctypes.c_int64, P(c_size_t)]
     lib.astro_nft_loss.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, ctypes.c_int64,
                                    c_int32, c_float, c_float, c_float, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.astro_chunk_attn_bwd_full_workspace_bytes.argtypes = [c_void_p, c_int32, P(c_size_t)]
+    lib.astro_chunk_attn_bwd_full.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                              c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                              c_size_t, c_void_p]
     lib.astro_profile_begin.argtypes = []
     lib.astro_profile_end.argtypes = [P(astro_kernel_time_t), c_int32, P(c_int32)]
     lib.astro_calib_mfma.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
@@ -386,3 +391,44 @@ def astro_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, a_max: flo
                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "astro_nft_loss")
     return loss, grad
+
+
+def astro_chunk_attn_bwd_full_workspace_bytes(cache: KVCache, n_frames: int) -> int:
+    b = c_size_t(0)
+    _check(_lib.astro_chunk_attn_bwd_full_workspace_bytes(cache.handle, n_frames, byref(b)),
+           "astro_chunk_attn_bwd_full_workspace_bytes")
+    return b.value
+
+
+def astro_chunk_attn_bwd_full(cache: KVCache, q, k_chunk, v_chunk, out, lse, dout, n_frames: int,
+                              dq=None, dk_chunk=None, dv_chunk=None, dk_cache=None, dv_cache=None,
+                              workspace=None, stream=None):
+    """The backward without the detach.  Returns fp32 (dq, dk_chunk, dv_chunk [B, Nq, H, D],
+    dk_cache, dv_cache [B, C*T, H, D]); rows of empty slots of the last two stay as they were
+    (zero when allocated here)."""
+    for name, t in (("q", q), ("k_chunk", k_chunk), ("v_chunk", v_chunk), ("out", out), ("dout", dout)):
+        _check_chunk_tensor(cache, t, n_frames, name)
+    d = cache.desc
+    mk = lambda: torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dq = mk() if dq is None else dq
+    dk_chunk = mk() if dk_chunk is None else dk_chunk
+    dv_chunk = mk() if dv_chunk is None else dv_chunk
+    ring_shape = (d.batch, d.capacity_frames * cache.tokens_per_frame, d.heads, d.head_dim)
+    mkr = lambda: torch.zeros(ring_shape, dtype=torch.float32, device=q.device)
+    dk_cache = mkr() if dk_cache is None else dk_cache
+    dv_cache = mkr() if dv_cache is None else dv_cache
+    for name, t in (("dq", dq), ("dk_chunk", dk_chunk), ("dv_chunk", dv_chunk)):
+        _check_chunk_tensor(cache, t, n_frames, name, torch.float32)
+    for name, t in (("dk_cache", dk_cache), ("dv_cache", dv_cache)):
+        if tuple(t.shape) != ring_shape or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError(f"{name}: expected contiguous fp32 device tensor of shape {ring_shape}")
+    if lse.dtype != torch.float32 or not lse.is_contiguous():
+        raise ValueError("lse: expected contiguous fp32")
+    if workspace is None:
+        workspace = cache.workspace(astro_chunk_attn_bwd_full_workspace_bytes(cache, n_frames), q.device)
+    _check(_lib.astro_chunk_attn_bwd_full(cache.handle, _ptr(q), _ptr(k_chunk), _ptr(v_chunk), _ptr(out), _ptr(lse),
+                                          _ptr(dout), n_frames, _ptr(dq), _ptr(dk_chunk), _ptr(dv_chunk),
+                                          _ptr(dk_cache), _ptr(dv_cache), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "astro_chunk_attn_bwd_full")
+    return dq, dk_chunk, dv_chunk, dk_cache, dv_cache

@@ -44,10 +44,10 @@ DevGeom dev_geom(const astro_kvcache* c, int group = 1) {
 }
 
 struct Workspace {
-  size_t q_rot, kc_rot, dq_rot, dk_rot, scratch, total;
+  size_t q_rot, kc_rot, dq_rot, dk_rot, scratch, dk_hist_rot, total;
 };
 
-Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group) {
+Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group, bool ring_grads = false) {
   const RingGeometry& g = c->geo;
   const size_t nq = (size_t)n_frames * g.T;
   const size_t rot = align256((size_t)g.B * group * g.H * nq * g.D * g.elem_bytes());
@@ -66,6 +66,8 @@ Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group) {
     off += align256(sizeof(float) * (bwd ? f32_bwd_workspace_floats(d, (int)nq) : f32_fwd_workspace_floats(d, (int)nq)));
   else if (bwd)
     off += align256(bf16_bwd_workspace_bytes(d, (int)nq));
+  w.dk_hist_rot = off;
+  if (ring_grads) off += align256((size_t)g.B * g.H * g.rows_per_head() * g.D * sizeof(float));
   w.total = off;
   return w;
 }
@@ -219,7 +221,7 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
 
 int astro_kvcache_tables(const astro_kvcache_t* cache, int32_t* slot_frame, int32_t* slot_pos, int32_t* next_n) {
   if (!cache) return ASTRO_ERR_INVALID_ARG;
-  const auto& sf = cache->tables.slot_frame();
+  const std::vector<int32_t> sf = cache->tables.slot_frame();
   // the temporal rotary position of a resident frame is its absolute frame index
   if (slot_frame) std::memcpy(slot_frame, sf.data(), sf.size() * sizeof(int32_t));
   if (slot_pos) std::memcpy(slot_pos, sf.data(), sf.size() * sizeof(int32_t));
@@ -287,6 +289,45 @@ int astro_group_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_ch
   stream_ints(cache, &first, nullptr, nullptr, group);
   if (launch_rope_unscatter_f32(d, dq_rot, dq, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
   if (launch_rope_unscatter_f32(d, dk_rot, dk_chunk, n_frames, first, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  return ASTRO_OK;
+}
+
+int astro_chunk_attn_bwd_full_workspace_bytes(const astro_kvcache_t* cache, int32_t n_frames, size_t* bytes) {
+  if (!cache || !bytes) return ASTRO_ERR_INVALID_ARG;
+  if (n_frames < 1 || n_frames > cache->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
+  if (cache->geo.dtype != ASTRO_BF16) return ASTRO_ERR_UNSUPPORTED;
+  *bytes = carve(cache, n_frames, true, 1, true).total;
+  return ASTRO_OK;
+}
+
+int astro_chunk_attn_bwd_full(astro_kvcache_t* cache, const void* q, const void* k_chunk, const void* v_chunk,
+                              const void* out, const float* lse, const void* dout, int32_t n_frames, float* dq,
+                              float* dk_chunk, float* dv_chunk, float* dk_cache, float* dv_cache, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_chunk_call(cache, n_frames, 1);
+  if (rc != ASTRO_OK) return rc;
+  if (cache->geo.dtype != ASTRO_BF16) return ASTRO_ERR_UNSUPPORTED;
+  if (!dk_cache || !dv_cache) return ASTRO_ERR_INVALID_ARG;
+  const Workspace w = carve(cache, n_frames, true, 1, true);
+  if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return ASTRO_ERR_WORKSPACE;
+  // the detached backward first (it also leaves the row terms the ring-row kernels need) ...
+  const int rc2 = astro_group_attn_bwd(cache, q, k_chunk, v_chunk, out, lse, dout, n_frames, 1, dq, dk_chunk, dv_chunk,
+                                       workspace, workspace_bytes, hip_stream);
+  if (rc2 != ASTRO_OK) return rc2;
+  // ... then dK~, dV of the resident ring rows, and the inverse rotation at each slot's frame
+  char* ws = (char*)workspace;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames, 1);
+  const DevGeom d = dev_geom(cache);
+  float* dk_hist_rot = (float*)(ws + w.dk_hist_rot);
+  if (launch_attn_bwd_hist_bf16(d, op, lse, dout, dk_hist_rot, dv_cache, ws + w.scratch, stream) != hipSuccess)
+    return ASTRO_ERR_HIP;
+  StreamInts start, next;
+  for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
+    start.v[b] = b < cache->geo.B ? cache->tables.start(b) : 0;
+    next.v[b] = b < cache->geo.B ? cache->tables.next_n(b) : 0;
+  }
+  if (launch_rope_unscatter_ring_f32(d, dk_hist_rot, dk_cache, start, next, stream) != hipSuccess) return ASTRO_ERR_HIP;
   return ASTRO_OK;
 }
 

@@ -36,6 +36,9 @@ struct BwdParams {
   float* dq_rot;  // [B][H][Nq][D]
   float* dk_rot;  // [B][H][Nq][D]
   float* dv;      // [B, Nq, H, D]
+  float* dk_hist_rot;  // [B][H][C*T][D]   (only when hist_keys)
+  float* dv_hist;      // [B, C*T, H, D]
+  int hist_keys;       // dK/dV kernel: 0 = the chunk's keys, 1 = the resident ring rows (group must be 1)
   int H, Nq, BH, tiles;  // BH = candidates * heads; tiles = workgroups per pair of the kernel being launched
   int group;             // candidates per cache stream
   int64_t cache_rows;
@@ -336,15 +339,20 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int64_t bh = (int64_t)b * p.H + h;
-  const int jc = (item.tile * kWaves + wave) * 32 + i32;  // this lane's chunk key
-  const bool live = jc < p.Nq;
+  // this lane's key: a chunk row, or (non-detached backward) a resident ring row of the stream
+  const int n_keys = p.hist_keys ? p.hist_rows.v[b] : p.Nq;
+  if (item.tile * kWaves * 32 >= n_keys) return;  // whole workgroup, before any barrier
+  const int jc = (item.tile * kWaves + wave) * 32 + i32;
+  const bool live = jc < n_keys;
   const int ntiles = (p.Nq + KT - 1) / KT;
 
   Wave w;
   w.init(lane, p.scale_log2e);
   {
-    const __bf16* krow = p.kc_rot + (bh * p.Nq + (live ? jc : 0)) * D;
-    const __bf16* vrow = p.v_chunk + (((int64_t)b * p.Nq + (live ? jc : 0)) * p.H + h) * D;
+    const int j0 = live ? jc : 0;
+    const __bf16* krow = p.hist_keys ? p.k_cache + (bh * p.cache_rows + j0) * D : p.kc_rot + (bh * p.Nq + j0) * D;
+    const __bf16* vrow = p.hist_keys ? p.v_cache + (bh * p.cache_rows + j0) * D
+                                     : p.v_chunk + (((int64_t)b * p.Nq + j0) * p.H + h) * D;
 #pragma unroll
     for (int st = 0; st < Wave::QSTEPS; ++st) {
       bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
@@ -396,8 +404,9 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   }
 
   if (live) {
-    float* krow = p.dk_rot + (bh * p.Nq + jc) * D;
-    float* vrow = p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
+    float* krow = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + jc) * D : p.dk_rot + (bh * p.Nq + jc) * D;
+    float* vrow = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + jc) * p.H + h) * D
+                              : p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
 #pragma unroll
     for (int db = 0; db < Wave::DB; ++db)
 #pragma unroll
@@ -425,8 +434,8 @@ int bwd_variant() {
 }
 
 template <int D>
-hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
-                  float* dq_rot, float* dk_rot, float* dv, void* scratch, hipStream_t stream) {
+BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
+                      float* dq_rot, float* dk_rot, float* dv, void* scratch) {
   BwdParams p;
   p.q_rot = (const __bf16*)op.q_rot;
   p.kc_rot = (const __bf16*)op.kc_rot;
@@ -449,6 +458,16 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   p.group = op.group;
+  p.dk_hist_rot = nullptr;
+  p.dv_hist = nullptr;
+  p.hist_keys = 0;
+  return p;
+}
+
+template <int D>
+hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
+                  float* dq_rot, float* dk_rot, float* dv, void* scratch, hipStream_t stream) {
+  BwdParams p = make_params<D>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch);
   const int64_t n_rows = (int64_t)g.B * op.Nq * g.H;
   {
     ProfileScope prof("attn_bwd_delta", stream);
@@ -476,7 +495,32 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   return hipGetLastError();
 }
 
+template <int D>
+hipError_t launch_hist(const DevGeom& g, const AttnOperands& op, const float* lse, const void* dout, float* dk_hist_rot,
+                       float* dv_hist, const void* scratch, hipStream_t stream) {
+  BwdParams p = make_params<D>(g, op, nullptr, lse, dout, nullptr, nullptr, nullptr, const_cast<void*>(scratch));
+  p.dk_hist_rot = dk_hist_rot;
+  p.dv_hist = dv_hist;
+  p.hist_keys = 1;
+  int max_hist = 0;
+  for (int b = 0; b < g.B; ++b) max_hist = op.hist_rows.v[b] > max_hist ? op.hist_rows.v[b] : max_hist;
+  if (max_hist == 0) return hipSuccess;
+  const int ktile = kWaves * 32;
+  p.tiles = (max_hist + ktile - 1) / ktile;
+  ProfileScope prof("attn_bwd_dkv_hist_bf16", stream);
+  attn_bwd_dkv_kernel<D, true, false, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+  attn_bwd_dkv_kernel<D, false, true, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_attn_bwd_hist_bf16(const DevGeom& g, const AttnOperands& op, const float* lse, const void* dout,
+                                     float* dk_hist_rot, float* dv_hist, const void* scratch, hipStream_t stream) {
+  if (op.group != 1) return hipErrorInvalidValue;
+  if (g.D == 128) return launch_hist<128>(g, op, lse, dout, dk_hist_rot, dv_hist, scratch, stream);
+  return launch_hist<64>(g, op, lse, dout, dk_hist_rot, dv_hist, scratch, stream);
+}
 
 size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq) { return (size_t)g.B * g.H * Nq * sizeof(float); }
 

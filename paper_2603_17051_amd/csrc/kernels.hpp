@@ -60,6 +60,13 @@ hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, co
 hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* dst, int n_frames,
                                      const StreamInts& first_frame, hipStream_t stream);
 
+// The same for gradients of the ring rows: src [B][H][C*T][D] (rotated frame) -> dst
+// [B, C*T, H, D] w.r.t. the un-rotated keys; the frame a slot holds follows from start and
+// next_n (frames appended); rows of empty slots are not written.
+hipError_t launch_rope_unscatter_ring_f32(const DevGeom& g, const float* src, float* dst,
+                                          const StreamInts& start, const StreamInts& next_n,
+                                          hipStream_t stream);
+
 // Keys / values visible to a chunk: the resident ring rows (a prefix of the ring) and
 // the chunk's own rows.  With group > 1 the chunk tensors hold `group` candidate chunks per
 // cache stream (candidate c = b*group + g, DevGeom::B counts candidates); all candidates of
@@ -91,5 +98,12 @@ size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq);  // beyond q_rot / kc
 hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out,
                                 const float* lse, const void* dout, float* dq_rot, float* dk_rot,
                                 float* dv, void* scratch, hipStream_t stream);
+// Gradients of the ring rows (the non-detached backward): dk_hist_rot [B][H][C*T][D] w.r.t. the
+// rotated keys as cached, dv_hist [B, C*T, H, D]; rows of empty slots are not written.  Needs
+// the row terms launch_attn_bwd_bf16 left in `scratch` (same call sequence, same stream);
+// group must be 1.
+hipError_t launch_attn_bwd_hist_bf16(const DevGeom& g, const AttnOperands& op, const float* lse,
+                                     const void* dout, float* dk_hist_rot, float* dv_hist,
+                                     const void* scratch, hipStream_t stream);
 
 }  // namespace astro

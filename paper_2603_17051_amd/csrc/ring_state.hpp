@@ -53,25 +53,39 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   return ASTRO_OK;
 }
 
+#if defined(__HIPCC__)
+#define ASTRO_HOST_DEVICE __host__ __device__
+#else
+#define ASTRO_HOST_DEVICE
+#endif
+
 // Ring slot of the n-th frame appended to a stream since its reset: the first C
 // frames fill slots in order (so residents are always a prefix of the slots while
 // the ring fills); afterwards the sliding part wraps over slots S .. C-1, which
 // overwrites frame n - Lw, the oldest non-sink frame.
-inline int slot_of_frame_number(int64_t n, int C, int S) {
+ASTRO_HOST_DEVICE inline int slot_of_frame_number(int64_t n, int C, int S) {
   if (n < C) return (int)n;
   return S + (int)((n - S) % (C - S));
+}
+
+// The inverse: number (since the reset) of the frame slot s holds once next_n frames have been
+// appended, or -1 for an empty slot.  While the ring fills, slot s holds frame s; afterwards a
+// sink slot keeps its frame and sliding slot S + j holds the newest frame n with (n - S) mod Lw = j.
+ASTRO_HOST_DEVICE inline int64_t frame_number_in_slot(int s, int64_t next_n, int C, int S) {
+  if (s < S || next_n <= C) return s < next_n ? s : -1;
+  const int Lw = C - S, j = s - S;
+  return S + j + ((next_n - 1 - S - j) / Lw) * Lw;
 }
 
 class RingTables {
  public:
   RingTables(int B, int C, int S)
-      : B_(B), C_(C), S_(S), start_(B, 0), next_n_(B, 0), slot_frame_((size_t)B * C, -1) {}
+      : B_(B), C_(C), S_(S), start_(B, 0), next_n_(B, 0) {}
 
   void reset(int stream, int32_t start_frame) {
     for (int b = (stream < 0 ? 0 : stream); b < (stream < 0 ? B_ : stream + 1); ++b) {
       start_[b] = start_frame;
       next_n_[b] = 0;
-      for (int s = 0; s < C_; ++s) slot_frame_[(size_t)b * C_ + s] = -1;
     }
   }
   // true if appending n_frames to every stream keeps every absolute frame index in int32
@@ -81,22 +95,26 @@ class RingTables {
     return true;
   }
   void append(int n_frames) {
-    for (int b = 0; b < B_; ++b) {
-      for (int i = 0; i < n_frames; ++i) {
-        const int64_t n = next_n_[b];
-        slot_frame_[(size_t)b * C_ + slot_of_frame_number(n, C_, S_)] = (int32_t)(start_[b] + n);
-        next_n_[b] = (int32_t)(n + 1);
-      }
-    }
+    for (int b = 0; b < B_; ++b) next_n_[b] += n_frames;
   }
   int32_t start(int b) const { return start_[b]; }
   int32_t next_n(int b) const { return next_n_[b]; }
   int32_t resident(int b) const { return next_n_[b] < C_ ? next_n_[b] : C_; }
-  const std::vector<int32_t>& slot_frame() const { return slot_frame_; }
+  // absolute frame index held by every slot, [B][C], -1 = empty (closed form; the kernels that
+  // need a slot's frame use the same function)
+  std::vector<int32_t> slot_frame() const {
+    std::vector<int32_t> t((size_t)B_ * C_, -1);
+    for (int b = 0; b < B_; ++b)
+      for (int s = 0; s < C_; ++s) {
+        const int64_t n = frame_number_in_slot(s, next_n_[b], C_, S_);
+        if (n >= 0) t[(size_t)b * C_ + s] = (int32_t)(start_[b] + n);
+      }
+    return t;
+  }
 
  private:
   int B_, C_, S_;
-  std::vector<int32_t> start_, next_n_, slot_frame_;
+  std::vector<int32_t> start_, next_n_;
 };
 
 }  // namespace astro

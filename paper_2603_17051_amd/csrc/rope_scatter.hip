@@ -3,6 +3,7 @@
 // and by the attention pre-pass (queries and chunk keys rotated into the workspace).
 // HBM-bound: every element is read once and written once, 16 bytes per lane.
 #include "kernels.hpp"
+#include "ring_state.hpp"
 
 namespace astro {
 namespace {
@@ -99,21 +100,15 @@ __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const
 }
 
 // Gradient w.r.t. the un-rotated tensor = R(phi)^T * gradient w.r.t. the rotated one.
-__global__ void __launch_bounds__(kThreads) rope_unscatter_f32_kernel(DevGeom g, const float* __restrict__ src,
-                                                                      float* __restrict__ dst, int n_frames,
-                                                                      StreamInts first_frame) {
-  __shared__ float2 tab[kMaxBlockPairs];
-  const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
-  if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+// One block = one token row of one frame: src head-major rows [.][H][rows_per_head][D] -> dst
+// token-major [., rows_per_head, H, D]; tok0 = first token of the row within its stream.
+__device__ __forceinline__ void unrotate_row(const DevGeom& g, const float2* tab, bool rope, const float* __restrict__ src,
+                                             float* __restrict__ dst, int b, int h, int64_t tok0, int64_t rows_per_head) {
   const int cpr = g.D / 4;
-  const int64_t tok0 = (int64_t)fi * g.T + (int64_t)row * g.gw;
-  const int64_t Nq = (int64_t)n_frames * g.T;
   for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
     const int w = idx / cpr, c = idx % cpr;
-    const int64_t src_off = (((int64_t)b * g.H + h) * Nq + tok0 + w) * g.D + c * 4;
-    const int64_t dst_off = (((int64_t)b * Nq + tok0 + w) * g.H + h) * g.D + c * 4;
+    const int64_t src_off = (((int64_t)b * g.H + h) * rows_per_head + tok0 + w) * g.D + c * 4;
+    const int64_t dst_off = (((int64_t)b * rows_per_head + tok0 + w) * g.H + h) * g.D + c * 4;
     f32x4 x = *reinterpret_cast<const f32x4*>(src + src_off);
     if (rope) {
 #pragma unroll
@@ -126,6 +121,33 @@ __global__ void __launch_bounds__(kThreads) rope_unscatter_f32_kernel(DevGeom g,
     }
     *reinterpret_cast<f32x4*>(dst + dst_off) = x;
   }
+}
+
+// chunk gradients: frame fi of the chunk sits at absolute index first_frame + fi
+__global__ void __launch_bounds__(kThreads) rope_unscatter_f32_kernel(DevGeom g, const float* __restrict__ src,
+                                                                      float* __restrict__ dst, int n_frames,
+                                                                      StreamInts first_frame) {
+  __shared__ float2 tab[kMaxBlockPairs];
+  const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
+  if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+  unrotate_row(g, tab, rope, src, dst, b, h, (int64_t)fi * g.T + (int64_t)row * g.gw, (int64_t)n_frames * g.T);
+}
+
+// gradients of the ring rows: slot s of stream b holds the frame the closed form names; empty
+// slots are skipped (their rows of dst are not written)
+__global__ void __launch_bounds__(kThreads) rope_unscatter_ring_f32_kernel(DevGeom g, const float* __restrict__ src,
+                                                                           float* __restrict__ dst, StreamInts start,
+                                                                           StreamInts next_n) {
+  __shared__ float2 tab[kMaxBlockPairs];
+  const int slot = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int64_t n = frame_number_in_slot(slot, next_n.v[b], g.C, g.S);
+  if (n < 0) return;  // whole block
+  const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
+  if (rope) fill_block_table(tab, g, start.v[b] + (int)n, row);
+  unrotate_row(g, tab, rope, src, dst, b, h, (int64_t)slot * g.T + (int64_t)row * g.gw, (int64_t)g.C * g.T);
 }
 
 }  // namespace
@@ -162,6 +184,14 @@ hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* 
   dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
   ProfileScope prof("grad_rope_unstage", stream);
   rope_unscatter_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, n_frames, first_frame);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_unscatter_ring_f32(const DevGeom& g, const float* src, float* dst, const StreamInts& start,
+                                          const StreamInts& next_n, hipStream_t stream) {
+  dim3 grid(g.C * g.gh, g.H, g.B), block(kThreads);
+  ProfileScope prof("grad_rope_unstage_ring", stream);
+  rope_unscatter_ring_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, start, next_n);
   return hipGetLastError();
 }
 
