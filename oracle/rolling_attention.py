@@ -21,7 +21,10 @@ no tiling, no online softmax.  numpy matmul serves as the contraction step.
 The paper gives no attention formula, rotary embedding, chunk size or
 eviction order; the readings taken (all listed in the design notes) are:
 scaled dot-product softmax with 1/sqrt(D); every chunk query sees every chunk
-key; the first S frames after a reset are the sinks; eviction is FIFO over
+key (or, with `block_frames`, the chunk keys of its own and earlier blocks of
+that many frames: the block-causal mask at a finer block size, down to the
+frame-by-frame factorisation p(x_i | x_<i) of Sec. 3.1);
+the first S frames after a reset are the sinks; eviction is FIFO over
 non-sink frames; attention runs over the residents first and the append comes
 after; rotary embedding is 3-axis (frame, row, column) on interleaved adjacent
 pairs with per-axis frequencies base**(-j/n_axis), temporal position = the
@@ -145,10 +148,14 @@ class RingTableSim:
 # attention over the visible set
 # ----------------------------------------------------------------------------
 
-def _softmax_attention(qt, kt, v):
-    """qt [Nq, D], kt [Nk, D], v [Nk, D] -> P [Nq, Nk], O [Nq, D], LSE [Nq]."""
+def _softmax_attention(qt, kt, v, visible=None):
+    """qt [Nq, D], kt [Nk, D], v [Nk, D] -> P [Nq, Nk], O [Nq, D], LSE [Nq].
+    visible: optional bool [Nq, Nk]; a hidden key gets score -inf (probability 0).
+    Every row must see at least one key."""
     D = qt.shape[1]
     s = (qt @ kt.T) / np.sqrt(np.float64(D))
+    if visible is not None:
+        s = np.where(visible, s, -np.inf)
     m = s.max(axis=1, keepdims=True)
     e = np.exp(s - m)
     z = e.sum(axis=1, keepdims=True)
@@ -168,8 +175,9 @@ class RollingCacheOracle:
     def __init__(self, batch: int, heads: int, head_dim: int, grid_h: int, grid_w: int,
                  capacity_frames: int, sink_frames: int, rope_pairs: Sequence[int],
                  rope_base: float = 10000.0, start_frames: Optional[Iterable[int]] = None,
-                 cache_rounding: bool = False):
+                 cache_rounding: bool = False, block_frames: Optional[int] = None):
         assert 0 <= sink_frames < capacity_frames
+        assert block_frames is None or block_frames >= 1
         assert sum(rope_pairs) in (0, head_dim // 2)
         self.B, self.H, self.D = batch, heads, head_dim
         self.gh, self.gw = grid_h, grid_w
@@ -179,6 +187,10 @@ class RollingCacheOracle:
         self.pairs = tuple(int(p) for p in rope_pairs)
         self.base = float(rope_base)
         self.cache_rounding = cache_rounding  # diagnostic: bf16-round rotated cached keys
+        # None: every chunk query sees the whole chunk.  k: the chunk's frames form blocks of
+        # k frames (the last may be shorter); a query sees the chunk keys of its own block
+        # and of earlier blocks only.  The history is visible to every query either way.
+        self.block_frames = block_frames
         starts = [0] * batch if start_frames is None else [int(s) for s in start_frames]
         self.start = starts
         # per stream: list of (K_frame [T,H,D], V_frame [T,H,D]) by reference
@@ -233,6 +245,15 @@ class RollingCacheOracle:
         f0 = self.start[b] + len(self.history[b])
         return np.concatenate([self._phi(f0 + i) for i in range(n_frames)], 0)
 
+    def _visible(self, n_hist_rows: int, n_frames: int):
+        """bool [Nq, n_hist_rows + Nq] of the keys each chunk query sees, or None when
+        that is all of them."""
+        if self.block_frames is None or self.block_frames >= n_frames:
+            return None
+        block = (np.arange(n_frames * self.T) // self.T) // self.block_frames  # block of each chunk token
+        chunk = block[None, :] <= block[:, None]
+        return np.concatenate([np.ones((n_frames * self.T, n_hist_rows), dtype=bool), chunk], axis=1)
+
     def _pairs(self, streams, heads):
         bs = range(self.B) if streams is None else streams
         hs = range(self.H) if heads is None else heads
@@ -255,7 +276,7 @@ class RollingCacheOracle:
             kh, vh = self._context(b, h)
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[b, :, h, :], dtype=np.float64)], 0)
-            p, o, l = _softmax_attention(qt, kt, vv)
+            p, o, l = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
             out[b, :, h, :] = o
             lse[b, h, :] = l
             if return_probs:
@@ -286,7 +307,7 @@ class RollingCacheOracle:
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[b, :, h, :], dtype=np.float64)], 0)
             do = np.asarray(dout[b, :, h, :], dtype=np.float64)
-            p, o, _ = _softmax_attention(qt, kt, vv)
+            p, o, _ = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
             delta = (do * o).sum(axis=1, keepdims=True)
             dp = do @ vv.T
             ds = p * (dp - delta)
@@ -332,7 +353,7 @@ class RollingCacheOracle:
             kc = rope_rotate(np.asarray(k_chunk[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[c, :, h, :], dtype=np.float64)], 0)
-            _, o, l = _softmax_attention(qt, kt, vv)
+            _, o, l = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
             out[c, :, h, :] = o
             lse[c, h, :] = l
         return out, lse
@@ -357,7 +378,7 @@ class RollingCacheOracle:
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[c, :, h, :], dtype=np.float64)], 0)
             do = np.asarray(dout[c, :, h, :], dtype=np.float64)
-            p, o, _ = _softmax_attention(qt, kt, vv)
+            p, o, _ = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
             delta = (do * o).sum(axis=1, keepdims=True)
             ds = p * (do @ vv.T - delta)
             dq[c, :, h, :] = rope_rotate((scale * (ds @ kt))[:, None, :], -phi)[:, 0]
