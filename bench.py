@@ -84,9 +84,10 @@ def main() -> int:
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
 
-    def make_cache(w):
+    def make_cache(w, block_frames=0):
         cache = A.astro_kvcache_create(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames,
-                                       w.sink_frames, w.chunk_frames, w.rope_pairs, w.rope_base)
+                                       w.sink_frames, w.chunk_frames, w.rope_pairs, w.rope_base,
+                                       block_frames=block_frames)
         pk, pv = wl.history_frame_pool(w, 4)
         dk, dv = dev_bf16(pk), dev_bf16(pv)
         for n in range(min(w.resident_frames, w.capacity_frames)):
@@ -269,6 +270,42 @@ def main() -> int:
             "extra_gradient_bytes": int(2 * np.prod(ring_shape) * 4)}
         ce.close()
         del qe, ke, ve, de, oe, le, g3, gk, gv, wsf
+        # frame-by-frame causality inside the chunk (block_frames = 1), config-5 shape: a query sees the
+        # chunk keys of its own and earlier frames, T*T*Fc*(Fc+1)/2 of the Nq*Nq chunk pairs
+        ce = make_cache(we, block_frames=1)
+        qe, ke, ve, de = (dev_bf16(x) for x in wl.chunk_inputs(we, with_dout=True))
+        oe = torch.empty_like(qe)
+        le = torch.empty((we.batch, we.heads, we.n_q), dtype=torch.float32, device=dev)
+        g3 = [torch.empty(qe.shape, dtype=torch.float32, device=dev) for _ in range(3)]
+        wse = torch.empty(max(A.astro_chunk_attn_workspace_bytes(ce, we.chunk_frames)), dtype=torch.uint8, device=dev)
+
+        def causal_step():
+            A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+            A.astro_chunk_attn_bwd(ce, qe, ke, ve, oe, le, de, we.chunk_frames, *g3, wse)
+
+        for _ in range(2):
+            causal_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            causal_step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 10
+        A.astro_profile_begin()
+        for _ in range(5):
+            causal_step()
+        kt = {n: t / l for n, (l, t) in A.astro_profile_end().items()}
+        T_, Fc_ = we.tokens_per_frame, we.chunk_frames
+        pairs = T_ * T_ * Fc_ * (Fc_ + 1) / 2.0
+        per = we.head_dim * we.heads * we.batch
+        fl = ((4.0 + 6.0) * we.n_q * (we.n_k - we.n_q) + (4.0 + 10.0) * pairs) * per
+        extras["frame_causal_fwd_bwd"] = {
+            "fwd_bwd_ms": round(ms, 4), "fwd_bwd_tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+            "frac_bf16_mfma_peak": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+            "fwd_kernel_ms": round(kt["attn_fwd_bf16"], 4), "dq_kernel_ms": round(kt["attn_bwd_dq_bf16"], 4),
+            "dkv_kernel_ms": round(kt["attn_bwd_dkv_bf16"], 4)}
+        ce.close()
+        del qe, ke, ve, de, oe, le, g3, wse
         # fused clip-level loss: 24 (one group) and 192 candidate clips of 3 latent frames 16 x 60 x 104, bf16
         for n_clips in (24, 192):
             shape = (n_clips, 3 * 16 * 60 * 104)

@@ -67,7 +67,8 @@ typedef struct astro_kvcache_desc {
   int32_t rope_pairs_t, rope_pairs_h, rope_pairs_w; /* sum == D/2, or all three 0         */
   int32_t dtype;                      /* ASTRO_BF16 or ASTRO_F32                          */
   int32_t flags;                      /* 0 or ASTRO_FLAG_HOST_ONLY                        */
-  int32_t reserved_;                  /* set to 0                                         */
+  int32_t block_frames;               /* block size of the causal mask inside a chunk, in */
+                                      /* frames; 0 = the whole chunk is one block         */
   double rope_base;                   /* > 1, e.g. 10000                                  */
   void *k_storage, *v_storage;        /* device, sizes from astro_kvcache_bytes; layout   */
                                       /* [B][H][C*T][D] of dtype; may be NULL iff         */
@@ -119,6 +120,12 @@ int astro_chunk_attn_workspace_bytes(const astro_kvcache_t *cache, int32_t n_fra
  * stream, the chunk's queries (rotated at frame indices start_frame + next_n ...)
  * attend to all resident cache frames and to all keys of the chunk itself:
  *   out = softmax(Q~ K~^T / sqrt(D)) V,  lse = log-sum-exp of the scaled scores.
+ * With desc.block_frames = k > 0 the chunk's frames form blocks of k frames (the last
+ * may be shorter) and a query sees, of the chunk, only the keys of its own and of
+ * earlier blocks (block-causal attention at that block size; k = 1 is the frame-by-
+ * frame factorisation p(x_i | x_<i) of Sec. 3.1 evaluated for several frames in one
+ * call); resident frames stay visible to every query.  Every attention call of the
+ * handle (chunk, group, both backwards) uses the same mask.
  * q, k_chunk, v_chunk: device, un-rotated, [B, n_frames*T, H, D];
  * out: device [B, n_frames*T, H, D] (dtype of the cache); lse: device fp32
  * [B, H, n_frames*T].  Does not modify the cache or its tables (append does).

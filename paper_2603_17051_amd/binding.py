@@ -43,7 +43,7 @@ class astro_kvcache_desc_t(ctypes.Structure):
         ("grid_h", c_int32), ("grid_w", c_int32),
         ("capacity_frames", c_int32), ("sink_frames", c_int32), ("max_chunk_frames", c_int32),
         ("rope_pairs_t", c_int32), ("rope_pairs_h", c_int32), ("rope_pairs_w", c_int32),
-        ("dtype", c_int32), ("flags", c_int32), ("reserved_", c_int32),
+        ("dtype", c_int32), ("flags", c_int32), ("block_frames", c_int32),
         ("rope_base", c_double),
         ("k_storage", c_void_p), ("v_storage", c_void_p),
     ]
@@ -128,9 +128,9 @@ def _stream(stream) -> c_void_p:
 
 def make_desc(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
               rope_pairs=(0, 0, 0), rope_base=10000.0, dtype=ASTRO_BF16, flags=0,
-              k_storage=None, v_storage=None) -> astro_kvcache_desc_t:
+              k_storage=None, v_storage=None, block_frames=0) -> astro_kvcache_desc_t:
     return astro_kvcache_desc_t(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames,
-                                max_chunk_frames, rope_pairs[0], rope_pairs[1], rope_pairs[2], dtype, flags, 0,
+                                max_chunk_frames, rope_pairs[0], rope_pairs[1], rope_pairs[2], dtype, flags, block_frames,
                                 float(rope_base), _ptr(k_storage), _ptr(v_storage))
 
 
@@ -176,11 +176,11 @@ class KVCache:
 
 def astro_kvcache_create(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
                          rope_pairs=(0, 0, 0), rope_base=10000.0, dtype=ASTRO_BF16, host_only=False,
-                         device="cuda:0") -> KVCache:
+                         device="cuda:0", block_frames=0) -> KVCache:
     """Allocate the K/V storage with torch (unless host_only) and create the handle."""
     flags = ASTRO_FLAG_HOST_ONLY if host_only else 0
     desc = make_desc(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
-                     rope_pairs, rope_base, dtype, flags)
+                     rope_pairs, rope_base, dtype, flags, block_frames=block_frames)
     k_storage = v_storage = None
     if not host_only:
         kb, vb = astro_kvcache_bytes(desc)

@@ -114,6 +114,9 @@ AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w,
   op.v_cache = c->v_storage;
   op.Nq = n_frames * c->geo.T;
   op.group = group;
+  // a block size that covers the chunk is no mask at all
+  const int bf = c->geo.block_frames;
+  op.block_rows = (bf > 0 && bf < n_frames) ? bf * c->geo.T : 0;
   stream_ints(c, nullptr, nullptr, &op.hist_rows);
   return op;
 }
@@ -149,7 +152,6 @@ int astro_kvcache_create(const astro_kvcache_desc_t* desc, astro_kvcache_t** out
   RingGeometry g;
   const int rc = validate_desc(desc, &g);
   if (rc != ASTRO_OK) return rc;
-  if (desc->reserved_ != 0) return ASTRO_ERR_INVALID_ARG;
   astro_kvcache* c = new (std::nothrow) astro_kvcache(g, desc->k_storage, desc->v_storage);
   if (!c) return ASTRO_ERR_INVALID_ARG;
   if (!g.host_only) {

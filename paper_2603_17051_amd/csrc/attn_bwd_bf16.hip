@@ -41,6 +41,7 @@ struct BwdParams {
   int hist_keys;       // dK/dV kernel: 0 = the chunk's keys, 1 = the resident ring rows (group must be 1)
   int H, Nq, BH, tiles;  // BH = candidates * heads; tiles = workgroups per pair of the kernel being launched
   int group;             // candidates per cache stream
+  int block_rows;        // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -93,11 +94,12 @@ struct DqWave {
         for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
   }
 
-  // One 64-key tile of which the first `live` keys exist (wave-uniform).  Rows past the end
-  // of a segment are zero in LDS; their score is replaced so that P and dS are exactly 0
-  // (left alone, P = exp(0 - LSE) could overflow for a query whose logits are all very
-  // negative, and inf * 0 would poison dQ~ = dS K~).
-  __device__ __forceinline__ void tile(const char* ks, const char* vs, int live) {
+  // One 64-key tile of which the first `live` keys count for lane's query qb (live_min,
+  // wave-uniform: the fewest over the wave).  The others lie past the end of their segment
+  // (zero rows in LDS) or in a causal block the query does not see; their score is replaced
+  // so that P and dS are exactly 0 (left alone, P = exp(0 - LSE) could overflow for a query
+  // whose logits are all very negative, and inf * 0 would poison dQ~ = dS K~).
+  __device__ __forceinline__ void tile(const char* ks, const char* vs, const int (&live)[NQB], int live_min) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -108,11 +110,11 @@ struct DqWave {
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) s[qb] = mfma32(ak, qreg[qb][st], st == 0 ? zero : s[qb]);
       }
-      if (live < 32 * (kb + 1)) {
+      if (live_min < 32 * (kb + 1)) {
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) s[qb][r] = 32 * kb + acc_row(r, g) >= live ? kNegBig : s[qb][r];
+          for (int r = 0; r < 16; ++r) s[qb][r] = 32 * kb + acc_row(r, g) >= live[qb] ? kNegBig : s[qb][r];
       }
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
@@ -166,10 +168,23 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int hist = p.hist_rows.v[pair.cache_b];
-  const int hist_tiles = (hist + KT - 1) / KT;
-  const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
   const int q0 = (item.tile * kWaves + wave) * 32 * NQB;
   const int64_t bh = (int64_t)b * p.H + h;
+  // chunk rows each of this lane's queries sees, the fewest any lane of the wave sees (its
+  // first query) and the most any wave of the workgroup sees (its last query)
+  const int q_last = p.Nq - 1;
+  int vis[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int q = q0 + 32 * qb + i32;
+    vis[qb] = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, p.block_rows);
+  }
+  const int q_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32 * NQB;
+  const int vis_wave = visible_chunk_rows(q_wave < q_last ? q_wave : q_last, p.Nq, p.block_rows);
+  const int q_wg = (item.tile + 1) * kWaves * 32 * NQB - 1;
+  const int vis_wg = visible_chunk_rows(q_wg < q_last ? q_wg : q_last, p.Nq, p.block_rows);
+  const int hist_tiles = (hist + KT - 1) / KT;
+  const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
 
   Wave w;
   w.init(lane, p.scale_log2e);
@@ -219,7 +234,10 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   for (int t = 0; t < ntiles; ++t) {
     if (t + 1 < ntiles) issue(t + 1);
     const char* kbuf = lds + (t & 1) * 2 * TILE_BYTES;
-    w.tile(kbuf, kbuf + TILE_BYTES, t < hist_tiles ? hist - t * KT : p.Nq - (t - hist_tiles) * KT);
+    int live[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) live[qb] = t < hist_tiles ? hist - t * KT : vis[qb] - (t - hist_tiles) * KT;
+    w.tile(kbuf, kbuf + TILE_BYTES, live, t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
     wait_vmem();
     __syncthreads();
   }
@@ -270,7 +288,10 @@ struct DkvWave {
   }
 
   // One tile of 64 queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
-  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, const float* delta_t) {
+  // Tile rows below `first` (per lane; first_max, wave-uniform, = the largest over the wave)
+  // are queries of an earlier causal block than this lane's key: they do not see it, P = 0.
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, const float* delta_t,
+                                       int first, int first_max) {
 #pragma unroll
     for (int qb = 0; qb < KT / 32; ++qb) {
       // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
@@ -279,6 +300,10 @@ struct DkvWave {
       f32x16 s, dp;
 #pragma unroll
       for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(qs, addr.row[st], qb), kreg[st], st == 0 ? zero : s);
+      if (first_max > 32 * qb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 32 * qb + acc_row(r, g) < first ? kNegBig : s[r];
+      }
       __builtin_amdgcn_sched_barrier(0);
       bf16x8 pb[2];
 #pragma unroll
@@ -345,6 +370,14 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   const int jc = (item.tile * kWaves + wave) * 32 + i32;
   const bool live = jc < n_keys;
   const int ntiles = (p.Nq + KT - 1) / KT;
+  // first query row that sees this lane's key (ring rows are seen by every query), the
+  // largest over the wave (its last key) and the smallest over the workgroup (its first key)
+  const int block_rows = p.hist_keys ? 0 : p.block_rows;
+  const int j_last = n_keys - 1;
+  const int first_q = first_query_row_seeing(jc < j_last ? jc : j_last, block_rows);
+  const int j_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32 + 31;
+  const int first_q_wave = first_query_row_seeing(j_wave < j_last ? j_wave : j_last, block_rows);
+  const int t_begin = first_query_row_seeing(item.tile * kWaves * 32, block_rows) / KT;
 
   Wave w;
   w.init(lane, p.scale_log2e);
@@ -383,12 +416,12 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
     ts.issue(q_rows, off_q, t * KT, qbuf);
     ts.issue(do_rows, off_do, t * KT, qbuf + TILE_BYTES);
   };
-  issue(0);
-  if (threadIdx.x < 2 * KT) rowterms[threadIdx.x] = rowterm(0);
+  issue(t_begin);
+  if (threadIdx.x < 2 * KT) rowterms[(t_begin & 1) * 2 * KT + threadIdx.x] = rowterm(t_begin);
   wait_vmem();
   __syncthreads();
 
-  for (int t = 0; t < ntiles; ++t) {
+  for (int t = t_begin; t < ntiles; ++t) {
     const bool more = t + 1 < ntiles;
     float rt = 0.f;
     if (more) {
@@ -397,7 +430,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
     }
     const char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
     const float* terms = rowterms + (t & 1) * 2 * KT;
-    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + KT);
+    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + KT, first_q - t * KT, first_q_wave - t * KT);
     if (more && threadIdx.x < 2 * KT) rowterms[((t + 1) & 1) * 2 * KT + threadIdx.x] = rt;
     wait_vmem();
     __syncthreads();
@@ -458,6 +491,7 @@ BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out,
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   p.group = op.group;
+  p.block_rows = op.block_rows;
   p.dk_hist_rot = nullptr;
   p.dv_hist = nullptr;
   p.hist_keys = 0;

@@ -14,6 +14,7 @@ struct F32Operands {
   const float* k_cache;
   const float* v_cache;
   int H, D, Nq, nk_stride, group;
+  int block_rows;  // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;
   float scale;
   StreamInts hist_rows;
@@ -48,12 +49,18 @@ __device__ float block_reduce(float x, bool is_max, float* red) {
   return r;
 }
 
-// S[q][j] = scale * <q~_q, k~_j>; grid (ceil(nk_stride/256), Nq, B*H)
+// S[q][j] = scale * <q~_q, k~_j>; grid (ceil(nk_stride/256), Nq, B*H).  A chunk key in a later
+// causal block than the query gets a score so low that every later step sees probability 0.
 __global__ void scores_kernel(F32Operands p, float* s) {
   const int bh = blockIdx.z, b = bh / p.H, h = bh % p.H, q = blockIdx.y;
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const int nk = p.hist_rows.v[b / p.group] + p.Nq;
+  const int hist = p.hist_rows.v[b / p.group];
+  const int nk = hist + p.Nq;
   if (j >= nk) return;
+  if (p.block_rows > 0 && j >= hist && (j - hist) / p.block_rows > q / p.block_rows) {
+    score_row(s, p, bh, q)[j] = -3.0e38f;
+    return;
+  }
   const float* qr = p.q_rot + ((int64_t)bh * p.Nq + q) * p.D;
   const float* kr = key_row(p, b, h, j);
   float acc = 0.f;
@@ -159,6 +166,7 @@ F32Operands make_operands(const DevGeom& g, const AttnOperands& op) {
   p.cache_rows = (int64_t)g.C * g.T;
   p.scale = (float)(1.0 / sqrt((double)g.D));
   p.group = op.group;
+  p.block_rows = op.block_rows;
   p.hist_rows = op.hist_rows;
   return p;
 }

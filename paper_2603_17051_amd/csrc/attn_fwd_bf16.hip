@@ -24,8 +24,6 @@
 // both the row maximum and the 64 accumulator multiplies of a rescale leave the common path.
 // MFMA and vector-ALU work of one wave do not overlap on this hardware; the overlap
 // comes from three workgroups (three waves per SIMD) being resident per CU.
-#include <cstdlib>
-
 #include "kernels.hpp"
 #include "mfma_common.hpp"
 
@@ -44,6 +42,7 @@ struct FwdParams {
   __bf16* out;
   float* lse;
   int H, Nq, BH, q_tiles, group;  // BH = candidates * heads; group = candidates per cache stream
+  int block_rows;                 // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;  // C*T
   float scale_log2e, scale;
   StreamInts hist_rows;
@@ -100,38 +99,38 @@ struct FwdWave {
     for (int st = 0; st < QSTEPS; ++st) kf[st] = read_rows8<D>(ks, addr.row[st], 0);
   }
 
-  // One 32-key tile: kf = its K operands, vs = its V rows in LDS; dead_keys (wave-uniform,
-  // only looked at when kTail) = number of rows at the tile's end that are past the segment.
-  // S^T tile of 32 keys x this wave's 32 queries from K operands in registers; with kTail,
-  // the dead_keys rows at the tile's end that lie past their segment (K and V rows zero in
-  // LDS) get a score that makes their probability exactly 0.
+  // S^T tile of 32 keys x this wave's 32 queries from K operands in registers.  With kTail
+  // and any_dead (wave-uniform), only the first `live` rows of the tile count for this lane's
+  // query: the others lie past their segment (K and V rows zero in LDS) or in a causal block
+  // the query does not see, and get a score that makes their probability exactly 0.
   template <bool kTail>
-  __device__ __forceinline__ f32x16 scores(const bf16x8 (&kf)[QSTEPS], int dead_keys) const {
+  __device__ __forceinline__ f32x16 scores(const bf16x8 (&kf)[QSTEPS], int live, bool any_dead) const {
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 s;
 #pragma unroll
     for (int st = 0; st < QSTEPS; ++st) s = mfma32(kf[st], qreg[st], st == 0 ? zero : s);
-    if (kTail && dead_keys > 0) {
+    if (kTail && any_dead) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = acc_row(r, g) >= KT - dead_keys ? kNegBig : s[r];
+      for (int r = 0; r < 16; ++r) s[r] = acc_row(r, g) >= live ? kNegBig : s[r];
     }
     return s;
   }
 
-  // One 32-key tile: kf = its K operands (read from ks), vs = its V rows in LDS; dead_keys
-  // is wave-uniform and only looked at when kTail.
+  // One 32-key tile: kf = its K operands (read from ks), vs = its V rows in LDS; live (per
+  // lane) and any_dead (wave-uniform) are only looked at when kTail.
   template <bool kTail>
-  __device__ __forceinline__ void tile(const bf16x8 (&kf)[QSTEPS], const char* ks, const char* vs, int dead_keys) {
+  __device__ __forceinline__ void tile(const bf16x8 (&kf)[QSTEPS], const char* ks, const char* vs, int live,
+                                       bool any_dead) {
     // Probabilities relative to the current reference.  No maximum is taken on the common
     // path: a tile whose logits outgrow the reference shows up as a huge (or infinite) row
     // sum; only then the scores are computed again (the first copy is gone: the exponentials
     // are taken in place), the reference is raised and the probabilities are redone.
     bf16x8 pb[2];
-    float sum = probabilities(scores<kTail>(kf, dead_keys), pb);
+    float sum = probabilities(scores<kTail>(kf, live, any_dead), pb);
     if (__builtin_expect(__any(!(sum <= kSumLimit)), 0)) {
       bf16x8 kf2[QSTEPS];
       read_k(ks, kf2);
-      const f32x16 s = scores<kTail>(kf2, dead_keys);
+      const f32x16 s = scores<kTail>(kf2, live, any_dead);
       float mx = fmaxf(s[0], s[1]);
 #pragma unroll
       for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
@@ -167,13 +166,17 @@ struct FwdWave {
   }
 };
 
-template <int D, int kStages, int kWaves, int OCC>
+// kCausal: the chunk has causal blocks (block_rows > 0), so the chunk rows a query sees differ
+// from lane to lane; without it that count is the uniform Nq and costs no vector register.
+template <int D, int kStages, int kWaves, int OCC, bool kCausal>
 __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdParams p) {
   using Wave = FwdWave<D>;
   constexpr int kAhead = kStages - 1;  // tiles in flight ahead of the one being processed
   constexpr int TILE_BYTES = KT * D * 2;
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char lds[kStages * STAGE_BYTES];
+  // per-lane count of visible chunk rows: kept in LDS, not in a register the tile loop has no room for
+  __shared__ int vis_lds[kCausal ? kWaves * 64 : 1];
 
   const WorkItem item = work_item(p.q_tiles, p.BH, true);
   if (!item.valid) return;
@@ -182,10 +185,19 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int hist = p.hist_rows.v[pair.cache_b];
-  // key tiles: first the resident ring rows, then the chunk's rows, each with its own tail
-  const int hist_tiles = (hist + KT - 1) / KT;
-  const int ntiles = hist_tiles + (p.Nq + KT - 1) / KT;
   const int q = (item.tile * kWaves + wave) * 32 + i32;
+  // chunk rows this lane's query sees, the fewest any lane of the wave sees (its first
+  // query) and the most any wave of the workgroup sees (its last query)
+  const int q_last = p.Nq - 1;
+  const int block_rows = kCausal ? p.block_rows : 0;
+  const int q_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32;
+  const int q_wg = (item.tile + 1) * kWaves * 32 - 1;
+  const int vis_wave = visible_chunk_rows(q_wave < q_last ? q_wave : q_last, p.Nq, block_rows);
+  const int vis_wg = visible_chunk_rows(q_wg < q_last ? q_wg : q_last, p.Nq, block_rows);
+  if constexpr (kCausal) vis_lds[threadIdx.x] = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, block_rows);
+  // key tiles: first the resident ring rows, then the chunk rows the workgroup sees, each with its own tail
+  const int hist_tiles = (hist + KT - 1) / KT;
+  const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
   const int64_t bh = (int64_t)b * p.H + h;
 
   Wave w;
@@ -222,9 +234,16 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     ts.issue(ks, off_dense, row0, stage);
     ts.issue(vs, in_hist ? off_dense : off_vchunk, row0, stage + TILE_BYTES);
   };
-  auto dead_in = [&](int t) __attribute__((always_inline)) {
-    const int live = t < hist_tiles ? hist - t * KT : p.Nq - (t - hist_tiles) * KT;
-    return live >= KT ? 0 : KT - live;
+  // rows of tile t that count for this lane, and whether any lane of the wave has fewer than all
+  auto live_in = [&](int t) __attribute__((always_inline)) {
+    if (t < hist_tiles) return hist - t * KT;
+    if constexpr (kCausal)
+      return vis_lds[threadIdx.x] - (t - hist_tiles) * KT;  // own entry: no barrier needed
+    else
+      return vis_wave - (t - hist_tiles) * KT;
+  };
+  auto any_dead_in = [&](int t) __attribute__((always_inline)) {
+    return (t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT) < KT;
   };
   // Invariant at the top of tile t: tiles t .. t+kAhead-1 have landed and are visible to
   // every wave except the last of them, whose loads may still be in flight; the stage of
@@ -256,9 +275,9 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
       issue(t + kAhead, refill);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == kGeneric)
-      w.template tile<true>(kf, stage, stage + TILE_BYTES, dead_in(t));
+      w.template tile<true>(kf, stage, stage + TILE_BYTES, live_in(t), any_dead_in(t));
     else
-      w.template tile<false>(kf, stage, stage + TILE_BYTES, 0);
+      w.template tile<false>(kf, stage, stage + TILE_BYTES, KT, false);
     // keep the next tile's K reads behind this tile's last MFMA: started earlier they
     // would need registers that are not there
     __builtin_amdgcn_sched_barrier(0);
@@ -300,7 +319,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   }
 }
 
-template <int D, int kStages, int kWaves, int OCC>
+template <int D, int kStages, int kWaves, int OCC, bool kCausal>
 hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* lse, hipStream_t stream) {
   FwdParams p;
   p.q_rot = (const __bf16*)op.q_rot;
@@ -317,26 +336,26 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   p.group = op.group;
+  p.block_rows = op.block_rows;
   const int qtile = kWaves * 32;
   p.BH = g.B * g.H;
   p.q_tiles = (op.Nq + qtile - 1) / qtile;
   dim3 grid(work_grid_size(p.q_tiles, p.BH));
   ProfileScope prof("attn_fwd_bf16", stream);
-  attn_fwd_bf16_kernel<D, kStages, kWaves, OCC><<<grid, dim3(kWaves * 64), 0, stream>>>(p);
+  attn_fwd_bf16_kernel<D, kStages, kWaves, OCC, kCausal><<<grid, dim3(kWaves * 64), 0, stream>>>(p);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, hipStream_t stream) {
-  static const int variant = [] {
-    const char* e = getenv("ASTRO_FWD_VARIANT");
-    return e ? atoi(e) : 0;
-  }();
-  if (g.D == 128) {
-    return launch<128, 3, 4, 3>(g, op, out, lse, stream);
-  }
-  return launch<64, 3, 4, 3>(g, op, out, lse, stream);
+  // The causal instantiation needs a few registers more than three workgroups per CU leave at
+  // D = 128 (it would reload a Q fragment from scratch in every tile: 4.0 ms instead of 3.5 ms
+  // at the 12-head, 1560-token, 21-frame shape), so it runs two workgroups per CU there.
+  const bool causal = op.block_rows > 0;
+  if (g.D == 128)
+    return causal ? launch<128, 3, 4, 2, true>(g, op, out, lse, stream) : launch<128, 3, 4, 3, false>(g, op, out, lse, stream);
+  return causal ? launch<64, 3, 4, 3, true>(g, op, out, lse, stream) : launch<64, 3, 4, 3, false>(g, op, out, lse, stream);
 }
 
 }  // namespace astro

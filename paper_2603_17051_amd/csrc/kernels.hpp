@@ -79,6 +79,7 @@ struct AttnOperands {
   const void* v_cache;  // [B][H][C*T][D]
   int Nq;
   int group;             // candidates per cache stream (1 = plain chunk attention)
+  int block_rows;        // causal block inside the chunk, in token rows; 0 = none (whole chunk)
   StreamInts hist_rows;  // resident ring rows per CACHE stream
 };
 

@@ -217,6 +217,18 @@ __device__ __forceinline__ PairIndex split_pair(int pair, int H, int group) {
   return x;
 }
 
+// Causal blocks inside the chunk (block_rows token rows each, 0 = the whole chunk is one
+// block): chunk rows [0, visible_chunk_rows) are the keys query row q sees, and query rows
+// [first_query_row_seeing, Nq) are the queries that see key row j.
+__device__ __forceinline__ int visible_chunk_rows(int q, int Nq, int block_rows) {
+  if (block_rows == 0) return Nq;
+  const int end = (q / block_rows + 1) * block_rows;
+  return end < Nq ? end : Nq;
+}
+__device__ __forceinline__ int first_query_row_seeing(int j, int block_rows) {
+  return block_rows == 0 ? 0 : (j / block_rows) * block_rows;
+}
+
 // wait until this wave's outstanding global loads (including direct-to-LDS ones) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 // ... all but the N most recently issued ones (loads complete in issue order)

@@ -12,6 +12,7 @@ namespace astro {
 
 struct RingGeometry {
   int B, H, D, gh, gw, T, C, S, Lw, max_chunk;
+  int block_frames;  // causal block size inside a chunk, 0 = the whole chunk
   int n_t, n_h, n_w;
   int dtype;
   bool host_only;
@@ -39,6 +40,7 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   if (npairs != 0 && !(d->rope_base > 1.0)) return ASTRO_ERR_INVALID_ARG;
   if (d->dtype != ASTRO_BF16 && d->dtype != ASTRO_F32) return ASTRO_ERR_UNSUPPORTED;
   if (d->flags & ~ASTRO_FLAG_HOST_ONLY) return ASTRO_ERR_INVALID_ARG;
+  if (d->block_frames < 0) return ASTRO_ERR_INVALID_ARG;
   const bool host_only = (d->flags & ASTRO_FLAG_HOST_ONLY) != 0;
   if (!host_only && (!d->k_storage || !d->v_storage)) return ASTRO_ERR_INVALID_ARG;
   // token rows of one head's ring plus one chunk must index with int32
@@ -48,6 +50,7 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   g->gh = d->grid_h; g->gw = d->grid_w; g->T = d->grid_h * d->grid_w;
   g->C = d->capacity_frames; g->S = d->sink_frames; g->Lw = Lw;
   g->max_chunk = d->max_chunk_frames;
+  g->block_frames = d->block_frames;
   g->n_t = d->rope_pairs_t; g->n_h = d->rope_pairs_h; g->n_w = d->rope_pairs_w;
   g->dtype = d->dtype; g->host_only = host_only; g->rope_base = d->rope_base;
   return ASTRO_OK;

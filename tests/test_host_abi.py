@@ -54,6 +54,7 @@ GOOD = dict(batch=1, heads=2, head_dim=64, grid_h=8, grid_w=8, capacity_frames=4
     (dict(rope_pairs=(-1, 23, 10)), A.binding.ASTRO_ERR_INVALID_ARG),
     (dict(rope_base=1.0), A.binding.ASTRO_ERR_INVALID_ARG),
     (dict(dtype=7), A.binding.ASTRO_ERR_UNSUPPORTED),
+    (dict(block_frames=-1), A.binding.ASTRO_ERR_INVALID_ARG),
 ])
 def test_create_rejects_bad_descriptors(change, code):
     args = dict(GOOD)
@@ -61,6 +62,11 @@ def test_create_rejects_bad_descriptors(change, code):
     with pytest.raises(A.AstroError) as e:
         A.astro_kvcache_create(host_only=True, **args)
     assert e.value.code == code
+
+
+def test_any_non_negative_causal_block_size_is_accepted():
+    for bf in (0, 1, 2, 100):
+        A.astro_kvcache_create(host_only=True, block_frames=bf, **GOOD).close()
 
 
 def test_create_needs_storage_unless_host_only():
