@@ -23,6 +23,7 @@ struct astro_kvcache {
   float2* d_tab_h = nullptr;
   float2* d_tab_w = nullptr;
   int device = -1;
+  int n_cus = 256;
   astro_kvcache(const RingGeometry& g, void* k, void* v) : geo(g), tables(g.B, g.C, g.S), k_storage(k), v_storage(v) {}
 };
 
@@ -37,6 +38,7 @@ DevGeom dev_geom(const astro_kvcache* c, int group = 1) {
   DevGeom d;
   d.B = g.B * group; d.H = g.H; d.D = g.D; d.gh = g.gh; d.gw = g.gw; d.T = g.T; d.C = g.C; d.S = g.S;
   d.n_t = g.n_t; d.n_h = g.n_h; d.n_w = g.n_w;
+  d.n_cus = c->n_cus;
   d.inv_freq_t = c->d_inv_freq_t;
   d.tab_h = c->d_tab_h;
   d.tab_w = c->d_tab_w;
@@ -66,6 +68,8 @@ Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group, bool 
     off += align256(sizeof(float) * (bwd ? f32_bwd_workspace_floats(d, (int)nq) : f32_fwd_workspace_floats(d, (int)nq)));
   else if (bwd)
     off += align256(bf16_bwd_workspace_bytes(d, (int)nq));
+  else
+    off += align256(bf16_fwd_split_bytes(d, (int)nq));
   w.dk_hist_rot = off;
   if (ring_grads) off += align256((size_t)g.B * g.H * g.rows_per_head() * g.D * sizeof(float));
   w.total = off;
@@ -170,6 +174,7 @@ int astro_kvcache_create(const astro_kvcache_desc_t* desc, astro_kvcache_t** out
         tw[(size_t)w * g.n_w + j] = make_float2((float)std::cos(a), (float)std::sin(a));
       }
     bool ok = hipGetDevice(&c->device) == hipSuccess;
+    ok = ok && hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && c->n_cus > 0;
     ok = ok && hipMalloc((void**)&c->d_inv_freq_t, inv_t.size() * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->d_tab_h, th.size() * sizeof(float2)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->d_tab_w, tw.size() * sizeof(float2)) == hipSuccess;
@@ -259,7 +264,7 @@ int astro_group_attn_fwd(astro_kvcache_t* cache, const void* q, const void* k_ch
   if (cache->geo.dtype == ASTRO_F32)
     e = launch_attn_fwd_f32(d, op, (float*)out, lse, (float*)(ws + w.scratch), stream);
   else
-    e = launch_attn_fwd_bf16(d, op, out, lse, stream);
+    e = launch_attn_fwd_bf16(d, op, out, lse, w.total > w.scratch ? ws + w.scratch : nullptr, stream);
   return e == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
 }
 

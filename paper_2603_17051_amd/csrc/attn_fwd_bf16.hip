@@ -41,6 +41,11 @@ struct FwdParams {
   const __bf16* v_cache;
   __bf16* out;
   float* lse;
+  // key-range split: workgroup (pair, split, tile) walks the split's share of the key tiles and
+  // writes its own normalised output and log-sum-exp to part `split`; a merge launch combines them
+  int splits;
+  __bf16* out_part;  // [splits][B, Nq, H, D]
+  float* lse_part;   // [splits][B][H][Nq]
   int H, Nq, BH, q_tiles, group;  // BH = candidates * heads; group = candidates per cache stream
   int block_rows;                 // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;  // C*T
@@ -178,9 +183,10 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   // per-lane count of visible chunk rows: kept in LDS, not in a register the tile loop has no room for
   __shared__ int vis_lds[kCausal ? kWaves * 64 : 1];
 
-  const WorkItem item = work_item(p.q_tiles, p.BH, true);
+  const WorkItem item = work_item(p.q_tiles, p.BH * p.splits, true);
   if (!item.valid) return;
-  const PairIndex pair = split_pair(item.bh, p.H, p.group);
+  const int split = item.bh % p.splits;
+  const PairIndex pair = split_pair(item.bh / p.splits, p.H, p.group);
   const int b = pair.b, h = pair.h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
@@ -198,6 +204,9 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   // key tiles: first the resident ring rows, then the chunk rows the workgroup sees, each with its own tail
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
+  // this workgroup's share [t_begin, t_end) of them (all of them without a split)
+  const int t_begin = (int)((int64_t)split * ntiles / p.splits);
+  const int t_end = (int)((int64_t)(split + 1) * ntiles / p.splits);
   const int64_t bh = (int64_t)b * p.H + h;
 
   Wave w;
@@ -251,8 +260,8 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   constexpr int kLoadsPerTile = 2 * Streamer::kInsts;  // per wave
 #pragma unroll
   for (int t = 0; t < kAhead; ++t)
-    if (t < ntiles) issue(t, lds + t * STAGE_BYTES);
-  if (ntiles >= kAhead && kAhead > 1)
+    if (t_begin + t < t_end) issue(t_begin + t, lds + t * STAGE_BYTES);
+  if (t_end - t_begin >= kAhead && kAhead > 1)
     wait_vmem_except<kLoadsPerTile>();
   else
     wait_vmem();
@@ -271,7 +280,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == kHist)
       issue_hist(t + kAhead, refill);
-    else if (t + kAhead < ntiles)
+    else if (t + kAhead < t_end)
       issue(t + kAhead, refill);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == kGeneric)
@@ -282,7 +291,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     // would need registers that are not there
     __builtin_amdgcn_sched_barrier(0);
     // tile t+1 .. t+kAhead-1 must have landed before the next tile starts; the newest may stay in flight
-    if (kAhead > 1 && (MODE != kGeneric || t + kAhead < ntiles))
+    if (kAhead > 1 && (MODE != kGeneric || t + kAhead < t_end))
       wait_vmem_except<kLoadsPerTile>();
     else
       wait_vmem();
@@ -292,20 +301,27 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   auto group = [&](int t, auto mode_c) __attribute__((always_inline)) {
     constexpr bool kAll = decltype(mode_c)::value != kGeneric;  // all kStages tiles exist
     step(t, std::integral_constant<int, 0>{}, mode_c);
-    if (kStages > 1 && (kAll || t + 1 < ntiles)) step(t + 1, std::integral_constant<int, 1 % kStages>{}, mode_c);
-    if (kStages > 2 && (kAll || t + 2 < ntiles)) step(t + 2, std::integral_constant<int, 2 % kStages>{}, mode_c);
-    if (kStages > 3 && (kAll || t + 3 < ntiles)) step(t + 3, std::integral_constant<int, 3 % kStages>{}, mode_c);
+    if (kStages > 1 && (kAll || t + 1 < t_end)) step(t + 1, std::integral_constant<int, 1 % kStages>{}, mode_c);
+    if (kStages > 2 && (kAll || t + 2 < t_end)) step(t + 2, std::integral_constant<int, 2 % kStages>{}, mode_c);
+    if (kStages > 3 && (kAll || t + 3 < t_end)) step(t + 3, std::integral_constant<int, 3 % kStages>{}, mode_c);
     static_assert(kStages <= 4, "unroll more steps");
   };
-  int t = 0;
-  for (; t + kStages - 1 + kAhead < hist_tiles; t += kStages) group(t, std::integral_constant<int, kHist>{});
-  for (; t < ntiles; t += kStages) group(t, std::integral_constant<int, kGeneric>{});
+  int t = t_begin;
+  const int fast_end = hist_tiles < t_end ? hist_tiles : t_end;
+  for (; t + kStages - 1 + kAhead < fast_end; t += kStages) group(t, std::integral_constant<int, kHist>{});
+  for (; t < t_end; t += kStages) group(t, std::integral_constant<int, kGeneric>{});
 
-  // ---- epilogue: normalise, write O [B, Nq, H, D] bf16 and LSE [B, H, Nq]
+  // ---- epilogue: normalise, write O [B, Nq, H, D] bf16 and LSE [B, H, Nq] (of this split's keys)
   const float l_tot = sum_with_partner32(w.l_run);
   const float inv = 1.f / l_tot;
+  __bf16* out = p.out;
+  float* lse = p.lse;
+  if (p.splits > 1) {
+    out = p.out_part + (int64_t)split * ((int64_t)p.BH * p.Nq * D);
+    lse = p.lse_part + (int64_t)split * ((int64_t)p.BH * p.Nq);
+  }
   if (q < p.Nq) {
-    __bf16* orow = p.out + (((int64_t)b * p.Nq + q) * p.H + h) * D;
+    __bf16* orow = out + (((int64_t)b * p.Nq + q) * p.H + h) * D;
 #pragma unroll
     for (int db = 0; db < Wave::DB; ++db)
 #pragma unroll
@@ -315,12 +331,45 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
         for (int c = 0; c < 4; ++c) x[c] = (__bf16)(w.o[db][4 * rr + c] * inv);
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * rr + 4 * g) = x;
       }
-    if (g == 0) p.lse[bh * p.Nq + q] = w.mc * kLn2 + __logf(l_tot);
+    if (g == 0) lse[bh * p.Nq + q] = w.mc * kLn2 + __logf(l_tot);
   }
 }
 
+// Combine the per-split results: softmax over the union of the splits' keys is the average of the
+// splits' outputs weighted by exp(lse_s - lse).  One wave per (stream, query, head) row.
+template <int D>
+__global__ void __launch_bounds__(256) fwd_merge_kernel(FwdParams p, int64_t n_rows) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b*Nq + q)*H + h
+  if (row >= n_rows) return;
+  const int lane = threadIdx.x & 63;
+  const int h = (int)(row % p.H);
+  const int64_t bq = row / p.H;
+  const int q = (int)(bq % p.Nq);
+  const int64_t b = bq / p.Nq;
+  const int64_t lse_at = (b * p.H + h) * p.Nq + q;
+  const int64_t out_stride = (int64_t)p.BH * p.Nq * D, lse_stride = (int64_t)p.BH * p.Nq;
+  float m = kNegBig;
+  for (int s = 0; s < p.splits; ++s) m = fmaxf(m, p.lse_part[s * lse_stride + lse_at]);
+  float tot = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int s = 0; s < p.splits; ++s) {
+    const float w = __expf(p.lse_part[s * lse_stride + lse_at] - m);
+    tot += w;
+    if (lane < D / 2) {
+      const bf16x2 o = *reinterpret_cast<const bf16x2*>(p.out_part + s * out_stride + row * D + lane * 2);
+      a0 = fmaf(w, (float)o[0], a0);
+      a1 = fmaf(w, (float)o[1], a1);
+    }
+  }
+  const float inv = 1.f / tot;
+  if (lane < D / 2) {
+    const bf16x2 o = {(__bf16)(a0 * inv), (__bf16)(a1 * inv)};
+    *reinterpret_cast<bf16x2*>(p.out + row * D + lane * 2) = o;
+  }
+  if (lane == 0) p.lse[lse_at] = m + __logf(tot);
+}
+
 template <int D, int kStages, int kWaves, int OCC, bool kCausal>
-hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* lse, hipStream_t stream) {
+hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* lse, void* parts, hipStream_t stream) {
   FwdParams p;
   p.q_rot = (const __bf16*)op.q_rot;
   p.kc_rot = (const __bf16*)op.kc_rot;
@@ -340,22 +389,61 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   const int qtile = kWaves * 32;
   p.BH = g.B * g.H;
   p.q_tiles = (op.Nq + qtile - 1) / qtile;
-  dim3 grid(work_grid_size(p.q_tiles, p.BH));
-  ProfileScope prof("attn_fwd_bf16", stream);
-  attn_fwd_bf16_kernel<D, kStages, kWaves, OCC, kCausal><<<grid, dim3(kWaves * 64), 0, stream>>>(p);
+  // a launch that would leave the chip under two rounds of workgroups is split over the keys
+  p.splits = kCausal ? 1 : bf16_fwd_splits(g, op, parts != nullptr);
+  p.out_part = (__bf16*)parts;
+  p.lse_part = (float*)((char*)parts + (size_t)p.splits * p.BH * op.Nq * D * 2);
+  dim3 grid(work_grid_size(p.q_tiles, p.BH * p.splits));
+  {
+    ProfileScope prof("attn_fwd_bf16", stream);
+    attn_fwd_bf16_kernel<D, kStages, kWaves, OCC, kCausal><<<grid, dim3(kWaves * 64), 0, stream>>>(p);
+  }
+  if (p.splits > 1) {
+    const int64_t n_rows = (int64_t)p.BH * op.Nq;
+    ProfileScope prof("attn_fwd_merge", stream);
+    fwd_merge_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, hipStream_t stream) {
+// ---- key-range split of launches that cannot fill the chip -----------------------------------
+// The forward holds three workgroups per CU.  With fewer than two rounds of workgroups (one
+// stream of 12 heads and 37 query tiles is 444 workgroups on 768 places) each (pair, query
+// tile) is cut into `splits` key ranges, enough for two rounds, at most kMaxFwdSplits and
+// never less than kMinTilesPerSplit key tiles each.
+constexpr int kMaxFwdSplits = 8, kMinTilesPerSplit = 4, kFwdWorkgroupsPerCu = 3;
+
+static int fwd_work_items(const DevGeom& g, int Nq) { return ((Nq + 127) / 128) * g.B * g.H; }
+
+size_t bf16_fwd_split_bytes(const DevGeom& g, int Nq) {
+  if (fwd_work_items(g, Nq) >= 2 * kFwdWorkgroupsPerCu * g.n_cus) return 0;
+  return (size_t)kMaxFwdSplits * g.B * g.H * Nq * ((size_t)g.D * 2 + sizeof(float));
+}
+
+int bf16_fwd_splits(const DevGeom& g, const AttnOperands& op, bool have_parts) {
+  if (!have_parts || op.block_rows > 0) return 1;
+  const int items = fwd_work_items(g, op.Nq), places = kFwdWorkgroupsPerCu * g.n_cus;
+  if (items >= 2 * places) return 1;
+  int min_hist = INT32_MAX;
+  for (int b = 0; b < g.B / op.group; ++b) min_hist = op.hist_rows.v[b] < min_hist ? op.hist_rows.v[b] : min_hist;
+  const int tiles = (min_hist + KT - 1) / KT + (op.Nq + KT - 1) / KT;
+  int s = (2 * places + items - 1) / items;
+  if (s > kMaxFwdSplits) s = kMaxFwdSplits;
+  if (s > tiles / kMinTilesPerSplit) s = tiles / kMinTilesPerSplit;
+  return s < 1 ? 1 : s;
+}
+
+hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, void* parts,
+                                hipStream_t stream) {
   // The causal instantiation needs a few registers more than three workgroups per CU leave at
   // D = 128 (it would reload a Q fragment from scratch in every tile: 4.0 ms instead of 3.5 ms
   // at the 12-head, 1560-token, 21-frame shape), so it runs two workgroups per CU there.
   const bool causal = op.block_rows > 0;
   if (g.D == 128)
-    return causal ? launch<128, 3, 4, 2, true>(g, op, out, lse, stream) : launch<128, 3, 4, 3, false>(g, op, out, lse, stream);
-  return causal ? launch<64, 3, 4, 3, true>(g, op, out, lse, stream) : launch<64, 3, 4, 3, false>(g, op, out, lse, stream);
+    return causal ? launch<128, 3, 4, 2, true>(g, op, out, lse, parts, stream) : launch<128, 3, 4, 3, false>(g, op, out, lse, parts, stream);
+  return causal ? launch<64, 3, 4, 3, true>(g, op, out, lse, parts, stream) : launch<64, 3, 4, 3, false>(g, op, out, lse, parts, stream);
 }
 
 }  // namespace astro

@@ -31,6 +31,7 @@ struct StreamInts {
 // Geometry and rotary tables every kernel needs.
 struct DevGeom {
   int B, H, D, gh, gw, T, C, S;
+  int n_cus;  // compute units of the device the cache lives on
   int n_t, n_h, n_w;
   const double* inv_freq_t;  // [n_t]  frequency of each temporal pair (fp64)
   const float2* tab_h;       // [gh][n_h] (cos, sin) of row position * frequency
@@ -93,7 +94,11 @@ hipError_t launch_attn_bwd_f32(const DevGeom& g, const AttnOperands& op, const f
                                float* dv, float* scratch, hipStream_t stream);
 
 // ---- bf16 MFMA path ----------------------------------------------------------
-hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse,
+// `parts`: bf16_fwd_split_bytes() bytes of scratch for the per-split results of a launch that is
+// split over the keys (0 bytes when the shape fills the chip without), or null = never split.
+size_t bf16_fwd_split_bytes(const DevGeom& g, int Nq);
+int bf16_fwd_splits(const DevGeom& g, const AttnOperands& op, bool have_parts);
+hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, void* parts,
                                 hipStream_t stream);
 size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq);  // beyond q_rot / kc_rot
 hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out,

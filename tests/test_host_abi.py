@@ -112,7 +112,9 @@ def test_workspace_sizes_are_reported():
     c = A.astro_kvcache_create(host_only=True, **GOOD)
     f, b = A.astro_chunk_attn_workspace_bytes(c, 2)
     rot = 1 * 2 * 2 * 64 * 64 * 2  # B*H*Nq*D*2 bytes
-    assert f == 2 * rot
+    # rotated Q and K_chunk, plus -- for a shape that cannot fill the chip -- room for the
+    # results of up to 8 key-range splits (bf16 output rows and fp32 log-sum-exps)
+    assert f == 2 * rot + 8 * (1 * 2 * 2 * 64) * (64 * 2 + 4)
     assert b >= 2 * rot + 2 * 2 * rot
     with pytest.raises(A.AstroError):
         A.astro_chunk_attn_workspace_bytes(c, 3)
@@ -125,6 +127,10 @@ def test_group_workspace_scales_with_the_group_and_bad_groups_are_rejected():
     assert A.astro_group_attn_workspace_bytes(c, 2, 1) == (f1, b1)
     f4, b4 = A.astro_group_attn_workspace_bytes(c, 2, 4)
     assert f4 == 4 * f1 and b4 >= 4 * (b1 - 1024)
+    # enough work for two rounds of workgroups on 256 CUs: no split, so no room for its results
+    big = A.astro_kvcache_create(host_only=True, **dict(GOOD, batch=64, heads=32, grid_h=32, grid_w=32, head_dim=128, rope_pairs=(22, 21, 21)))
+    assert A.astro_chunk_attn_workspace_bytes(big, 1)[0] == 2 * 64 * 32 * 1024 * 128 * 2
+    big.close()
     for bad in (0, -1, binding.ASTRO_MAX_BATCH + 1):
         with pytest.raises(A.AstroError) as e:
             A.astro_group_attn_workspace_bytes(c, 2, bad)
