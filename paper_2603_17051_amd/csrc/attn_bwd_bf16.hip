@@ -262,9 +262,10 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
 
 // ---- dK, dV of the chunk's keys ---------------------------------------------------
 // DV / DK select which of the two gradients this instantiation accumulates: computing both
-// in one wave needs more registers than two resident waves per SIMD have, so the kernel is
-// launched once per gradient (S is recomputed in both).
-template <int D, bool DV, bool DK>
+// in one wave needs more registers than two resident waves per SIMD have, so every tile of
+// keys is taken by two workgroups, one per gradient (S is recomputed in both).
+// QT = query rows per LDS tile.
+template <int D, bool DV, bool DK, int QT>
 struct DkvWave {
   static constexpr int QSTEPS = D / 16;
   static constexpr int DB = D / 32;
@@ -287,13 +288,13 @@ struct DkvWave {
       }
   }
 
-  // One tile of 64 queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
+  // One tile of QT queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
   // Tile rows below `first` (per lane; first_max, wave-uniform, = the largest over the wave)
   // are queries of an earlier causal block than this lane's key: they do not see it, P = 0.
   __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, const float* delta_t,
                                        int first, int first_max) {
 #pragma unroll
-    for (int qb = 0; qb < KT / 32; ++qb) {
+    for (int qb = 0; qb < QT / 32; ++qb) {
       // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       // phase order keeps few values live: S -> P -> dV products, then dP -> dS -> dK products
@@ -350,15 +351,15 @@ struct DkvWave {
   }
 };
 
-template <int D, bool DV, bool DK, int OCC>
-__global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p) {
-  using Wave = DkvWave<D, DV, DK>;
-  constexpr int TILE_BYTES = KT * D * 2;
-  // Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [KT] and Delta [KT]
-  __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES + 4 * KT * 4];
+// Work of one workgroup, number `index` among those that accumulate this gradient.
+// lds: 4 * QT * D * 2 + 4 * QT * 4 bytes -- Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [QT] and Delta [QT].
+template <int D, bool DV, bool DK, int QT>
+__device__ __forceinline__ void dkv_workgroup(const BwdParams& p, int index, char* lds) {
+  using Wave = DkvWave<D, DV, DK, QT>;
+  constexpr int TILE_BYTES = QT * D * 2;
   float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
 
-  const WorkItem item = work_item(p.tiles, p.BH, false);
+  const WorkItem item = work_item(p.tiles, p.BH, false, index);
   if (!item.valid) return;
   const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -369,7 +370,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   if (item.tile * kWaves * 32 >= n_keys) return;  // whole workgroup, before any barrier
   const int jc = (item.tile * kWaves + wave) * 32 + i32;
   const bool live = jc < n_keys;
-  const int ntiles = (p.Nq + KT - 1) / KT;
+  const int ntiles = (p.Nq + QT - 1) / QT;
   // first query row that sees this lane's key (ring rows are seen by every query), the
   // largest over the wave (its last key) and the smallest over the workgroup (its first key)
   const int block_rows = p.hist_keys ? 0 : p.block_rows;
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
   const int first_q = first_query_row_seeing(jc < j_last ? jc : j_last, block_rows);
   const int j_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32 + 31;
   const int first_q_wave = first_query_row_seeing(j_wave < j_last ? j_wave : j_last, block_rows);
-  const int t_begin = first_query_row_seeing(item.tile * kWaves * 32, block_rows) / KT;
+  const int t_begin = first_query_row_seeing(item.tile * kWaves * 32, block_rows) / QT;
 
   Wave w;
   w.init(lane, p.scale_log2e);
@@ -400,24 +401,24 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
 
   const RowSegment q_rows = make_segment(p.q_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment do_rows = make_segment(p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, KT, kWaves> ts;
+  TileStreamer<D, QT, kWaves> ts;
   ts.init();
   const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
-  // thread < KT carries LSE*log2e of tile row `thread`, KT <= thread < 2KT its Delta;
+  // thread < QT carries LSE*log2e of tile row `thread`, QT <= thread < 2 QT its Delta;
   // rows past Nq get P = exp2(0 - big) = 0
   auto rowterm = [&](int tile) {
     const int t = threadIdx.x;
-    const int q = tile * KT + (t & (KT - 1));
-    if (t < KT) return q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    return (t < 2 * KT && q < p.Nq) ? p.delta[bh * p.Nq + q] : 0.f;
+    const int q = tile * QT + (t & (QT - 1));
+    if (t < QT) return q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    return (t < 2 * QT && q < p.Nq) ? p.delta[bh * p.Nq + q] : 0.f;
   };
   auto issue = [&](int t) {
     char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
-    ts.issue(q_rows, off_q, t * KT, qbuf);
-    ts.issue(do_rows, off_do, t * KT, qbuf + TILE_BYTES);
+    ts.issue(q_rows, off_q, t * QT, qbuf);
+    ts.issue(do_rows, off_do, t * QT, qbuf + TILE_BYTES);
   };
   issue(t_begin);
-  if (threadIdx.x < 2 * KT) rowterms[(t_begin & 1) * 2 * KT + threadIdx.x] = rowterm(t_begin);
+  if (threadIdx.x < 2 * QT) rowterms[(t_begin & 1) * 2 * QT + threadIdx.x] = rowterm(t_begin);
   wait_vmem();
   __syncthreads();
 
@@ -429,9 +430,9 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
       rt = rowterm(t + 1);
     }
     const char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
-    const float* terms = rowterms + (t & 1) * 2 * KT;
-    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + KT, first_q - t * KT, first_q_wave - t * KT);
-    if (more && threadIdx.x < 2 * KT) rowterms[((t + 1) & 1) * 2 * KT + threadIdx.x] = rt;
+    const float* terms = rowterms + (t & 1) * 2 * QT;
+    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + QT, first_q - t * QT, first_q_wave - t * QT);
+    if (more && threadIdx.x < 2 * QT) rowterms[((t + 1) & 1) * 2 * QT + threadIdx.x] = rt;
     wait_vmem();
     __syncthreads();
   }
@@ -454,6 +455,19 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
         if (DV) *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
       }
   }
+}
+
+// One launch for both gradients: the first tiles * BH workgroups accumulate dK (the longer
+// job: S, dP, dK), the rest dV (S, dV), so the two kinds fill the chip together instead of
+// each ending in its own partly filled round of workgroups.
+template <int D, int OCC, int QT>
+__global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * QT * D * 2 + 4 * QT * 4];
+  const int n = p.tiles * p.BH;
+  if ((int)blockIdx.x < n)
+    dkv_workgroup<D, false, true, QT>(p, (int)blockIdx.x, lds);
+  else
+    dkv_workgroup<D, true, false, QT>(p, (int)blockIdx.x - n, lds);
 }
 
 // tuning knob (environment ASTRO_BWD_VARIANT): 0 = 32 queries per wave and two workgroups per
@@ -523,8 +537,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   {
     ProfileScope prof("attn_bwd_dkv_bf16", stream);
     p.tiles = (op.Nq + ktile - 1) / ktile;
-    attn_bwd_dkv_kernel<D, true, false, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
-    attn_bwd_dkv_kernel<D, false, true, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+    attn_bwd_dkv_kernel<D, 2, 64><<<dim3(2 * work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
   }
   return hipGetLastError();
 }
@@ -542,8 +555,7 @@ hipError_t launch_hist(const DevGeom& g, const AttnOperands& op, const float* ls
   const int ktile = kWaves * 32;
   p.tiles = (max_hist + ktile - 1) / ktile;
   ProfileScope prof("attn_bwd_dkv_hist_bf16", stream);
-  attn_bwd_dkv_kernel<D, true, false, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
-  attn_bwd_dkv_kernel<D, false, true, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+  attn_bwd_dkv_kernel<D, 2, 64><<<dim3(2 * work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
   return hipGetLastError();
 }
 

@@ -183,9 +183,8 @@ struct WorkItem {
 };
 constexpr int kXcds = 8;
 __host__ __device__ inline int work_grid_size(int tiles_per_head, int BH) { return tiles_per_head * BH; }
-__device__ __forceinline__ WorkItem work_item(int tiles_per_head, int BH, bool by_xcd) {
+__device__ __forceinline__ WorkItem work_item(int tiles_per_head, int BH, bool by_xcd, int i) {
   WorkItem w;
-  const int i = (int)blockIdx.x;
   w.valid = i < tiles_per_head * BH;
   int j = i, first = 0;
   if (by_xcd && BH % kXcds == 0) {
@@ -196,6 +195,10 @@ __device__ __forceinline__ WorkItem work_item(int tiles_per_head, int BH, bool b
   w.bh = first + rel;
   w.tile = j - rel * tiles_per_head;
   return w;
+}
+
+__device__ __forceinline__ WorkItem work_item(int tiles_per_head, int BH, bool by_xcd) {
+  return work_item(tiles_per_head, BH, by_xcd, (int)blockIdx.x);
 }
 
 // A work item's pair index -> candidate, head and cache stream.  Pairs are ordered (cache
