@@ -1,7 +1,8 @@
 // Chunk attention backward with the cached context detached (Sec. 3.3), bf16 MFMA with
-// fp32 accumulation.  Three kernels, no atomics, deterministic:
-//   delta : Delta[q] = <dO_q, O_q>
+// fp32 accumulation.  Two kernels, no atomics, deterministic:
 //   dq    : one workgroup per query tile, walks ALL visible keys (ring + chunk):
+//             Delta[q] = <dO_q, O_q> (taken while the query's dO row is loaded, and
+//             written out for the second kernel),
 //             S^T = K Q~^T, P^T = exp(S^T/sqrt(D) - LSE), dP^T = V dO^T,
 //             dS^T = P^T o (dP^T - Delta), dQ~^T += K^T dS^T
 //   dkv   : one workgroup per tile of CHUNK keys, walks all query tiles:
@@ -46,29 +47,6 @@ struct BwdParams {
   float scale_log2e, scale;
   StreamInts hist_rows;
 };
-
-// one wave per (b, q, h): Delta = sum_d dO * O
-template <int D>
-__global__ void __launch_bounds__(256) delta_kernel(BwdParams p, int64_t n_rows) {
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (b*Nq + q)*H + h
-  if (row >= n_rows) return;
-  const int lane = threadIdx.x & 63;
-  float acc = 0.f;
-  if (lane < D / 2) {
-    const bf16x2 o = *reinterpret_cast<const bf16x2*>(p.out + row * D + lane * 2);
-    const bf16x2 d = *reinterpret_cast<const bf16x2*>(p.dout + row * D + lane * 2);
-    acc = (float)o[0] * (float)d[0] + (float)o[1] * (float)d[1];
-  }
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
-  if (lane == 0) {
-    const int h = (int)(row % p.H);
-    const int64_t bq = row / p.H;
-    const int q = (int)(bq % p.Nq);
-    const int b = (int)(bq / p.Nq);
-    p.delta[((int64_t)b * p.H + h) * p.Nq + q] = acc;
-  }
-}
 
 // ---- dQ -----------------------------------------------------------------------
 template <int D, int NQB>
@@ -193,20 +171,30 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
     const int q = q0 + 32 * qb + i32;
     const bool live = q < p.Nq;
     const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
-    const __bf16* drow = p.dout + (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
+    const int64_t token_row = (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
+    const __bf16* drow = p.dout + token_row;
+    const __bf16* orow = p.out + token_row;
+    // Delta = <dO_q, O_q>: this lane holds the halves 16*st + 8g .. +7 of the row, its
+    // partner lane the others
+    float dsum = 0.f;
 #pragma unroll
     for (int st = 0; st < Wave::QSTEPS; ++st) {
-      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x, o = x;
       if (live) {
         x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
         y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
+        o = *reinterpret_cast<const bf16x8*>(orow + st * 16 + g * 8);
       }
       w.qreg[qb][st] = x;
       w.doreg[qb][st] = y;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dsum = fmaf((float)y[j], (float)o[j], dsum);
     }
+    dsum = sum_with_partner32(dsum);
+    if (live && g == 0) p.delta[bh * p.Nq + q] = dsum;
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
     w.lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    w.delta[qb] = live ? p.delta[bh * p.Nq + q] : 0.f;
+    w.delta[qb] = dsum;
   }
 
   const RowSegment k_hist = make_segment(p.k_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
@@ -516,11 +504,6 @@ template <int D>
 hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
                   float* dq_rot, float* dk_rot, float* dv, void* scratch, hipStream_t stream) {
   BwdParams p = make_params<D>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch);
-  const int64_t n_rows = (int64_t)g.B * op.Nq * g.H;
-  {
-    ProfileScope prof("attn_bwd_delta", stream);
-    delta_kernel<D><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, stream>>>(p, n_rows);
-  }
   {
     ProfileScope prof("attn_bwd_dq_bf16", stream);
     if (bwd_variant() == 1) {
