@@ -219,15 +219,20 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   wait_vmem();
   __syncthreads();
 
-  for (int t = 0; t < ntiles; ++t) {
+  // two tiles per trip so that each LDS buffer is a compile-time offset of the operand reads
+  auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
     if (t + 1 < ntiles) issue(t + 1);
-    const char* kbuf = lds + (t & 1) * 2 * TILE_BYTES;
+    const char* kbuf = lds + decltype(buf_c)::value * 2 * TILE_BYTES;
     int live[NQB];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) live[qb] = t < hist_tiles ? hist - t * KT : vis[qb] - (t - hist_tiles) * KT;
     w.tile(kbuf, kbuf + TILE_BYTES, live, t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
     wait_vmem();
     __syncthreads();
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
 
 #pragma unroll
@@ -400,29 +405,38 @@ __device__ __forceinline__ void dkv_workgroup(const BwdParams& p, int index, cha
     if (t < QT) return q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
     return (t < 2 * QT && q < p.Nq) ? p.delta[bh * p.Nq + q] : 0.f;
   };
-  auto issue = [&](int t) {
-    char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
+  // tile t lives in buffer t % 2
+  auto issue = [&](int t, int buf) __attribute__((always_inline)) {
+    char* qbuf = lds + buf * 2 * TILE_BYTES;
     ts.issue(q_rows, off_q, t * QT, qbuf);
     ts.issue(do_rows, off_do, t * QT, qbuf + TILE_BYTES);
   };
-  issue(t_begin);
+  issue(t_begin, t_begin & 1);
   if (threadIdx.x < 2 * QT) rowterms[(t_begin & 1) * 2 * QT + threadIdx.x] = rowterm(t_begin);
   wait_vmem();
   __syncthreads();
 
-  for (int t = t_begin; t < ntiles; ++t) {
+  // two tiles per trip so that each LDS buffer is a compile-time offset of the operand reads
+  auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_c)::value;
     const bool more = t + 1 < ntiles;
     float rt = 0.f;
     if (more) {
-      issue(t + 1);
+      issue(t + 1, BUF ^ 1);
       rt = rowterm(t + 1);
     }
-    const char* qbuf = lds + (t & 1) * 2 * TILE_BYTES;
-    const float* terms = rowterms + (t & 1) * 2 * QT;
+    const char* qbuf = lds + BUF * 2 * TILE_BYTES;
+    const float* terms = rowterms + BUF * 2 * QT;
     w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + QT, first_q - t * QT, first_q_wave - t * QT);
-    if (more && threadIdx.x < 2 * QT) rowterms[((t + 1) & 1) * 2 * QT + threadIdx.x] = rt;
+    if (more && threadIdx.x < 2 * QT) rowterms[(BUF ^ 1) * 2 * QT + threadIdx.x] = rt;
     wait_vmem();
     __syncthreads();
+  };
+  int t = t_begin;
+  if (t & 1) step(t++, std::integral_constant<int, 1>{});
+  for (; t < ntiles; t += 2) {
+    step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
 
   if (live) {
