@@ -39,9 +39,25 @@ __global__ void __launch_bounds__(256, 2) calib_mfma_kernel(const bf16x8* __rest
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Four 16-byte loads in flight per lane, cache-bypassing loads and stores: the fastest of the
+// plain copies tried on this chip (6.0 TB/s read + write at 1 GiB; one load at a time with
+// default cache policy: 4.5 TB/s).
 __global__ void __launch_bounds__(256) calib_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, size_t n16) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  constexpr int kUnroll = 4;
+  const size_t span = (size_t)kUnroll * 256;
+  for (size_t base = (size_t)blockIdx.x * span; base < n16; base += (size_t)gridDim.x * span) {
+    f32x4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const size_t i = base + (size_t)u * 256 + threadIdx.x;
+      if (i < n16) v[u] = __builtin_nontemporal_load(src + i);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const size_t i = base + (size_t)u * 256 + threadIdx.x;
+      if (i < n16) __builtin_nontemporal_store(v[u], dst + i);
+    }
+  }
 }
 
 }  // namespace

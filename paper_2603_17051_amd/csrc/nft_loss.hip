@@ -1,7 +1,7 @@
 // Clip-level forward-process RL loss and its gradient w.r.t. the current velocity prediction
 // (Sec. 3.1 eq. (1)-(2), Sec. 3.3 reward normalisation, Sec. 3.4 selective KL; Alg. 1 Phase 2),
 // fused into one pass over the four velocity-shaped tensors: HBM-bound, every element is read
-// once (4 tensors) and its gradient written once.  Deterministic: per-block partial sums in a
+// once (4 tensors) and its gradient written once (cache-bypassing loads and stores).  Deterministic: per-block partial sums in a
 // workspace, summed in a fixed order by one block.
 #include "kernels.hpp"
 
@@ -52,7 +52,7 @@ template <>
 struct Chunk<__bf16> {
   static constexpr int N = 8;
   static __device__ __forceinline__ void load(const void* base, int64_t i, float (&x)[N]) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(base) + i);
+    const bf16x8 v = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(base) + i));
 #pragma unroll
     for (int j = 0; j < N; ++j) x[j] = (float)v[j];
   }
@@ -61,7 +61,7 @@ template <>
 struct Chunk<float> {
   static constexpr int N = 4;
   static __device__ __forceinline__ void load(const void* base, int64_t i, float (&x)[N]) {
-    const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i);
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i));
 #pragma unroll
     for (int j = 0; j < N; ++j) x[j] = v[j];
   }
@@ -100,7 +100,8 @@ __global__ void __launch_bounds__(kThreads) nft_loss_kernel(NftParams p) {
     }
     float* go = p.grad + base + e;
 #pragma unroll
-    for (int j = 0; j < N; j += 4) *reinterpret_cast<f32x4*>(go + j) = f32x4{g[j], g[j + 1], g[j + 2], g[j + 3]};
+    for (int j = 0; j < N; j += 4)
+      __builtin_nontemporal_store(f32x4{g[j], g[j + 1], g[j + 2], g[j + 3]}, reinterpret_cast<f32x4*>(go + j));
   }
   // block reduction of the three sums
   __shared__ float red[3][kThreads / 64];

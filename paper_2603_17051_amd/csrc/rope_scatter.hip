@@ -48,35 +48,69 @@ __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const
   const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
   const int h = blockIdx.y, b = blockIdx.z;
   const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
-  if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
   const int cpr = g.D / EPC;  // chunks per token row of one head
   const int dst_frame_row = ring ? ring_slot(next_n.v[b] + fi, g.C, g.S) * g.T : fi * g.T;
   const int64_t in_tok0 = ((int64_t)b * n_frames + fi) * g.T + (int64_t)row * g.gw;
   const int64_t out_row0 = ((int64_t)b * g.H + h) * rows_per_head + dst_frame_row + (int64_t)row * g.gw;
-  for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
-    const int w = idx / cpr, c = idx % cpr;
-    const int64_t in_off = ((in_tok0 + w) * g.H + h) * g.D + c * EPC;
-    const int64_t out_off = (out_row0 + w) * g.D + c * EPC;
-    if constexpr (sizeof(Elem) == 2) {
-      bf16x8 xa = *reinterpret_cast<const bf16x8*>(a_in + in_off);
-      bf16x8 xb = *reinterpret_cast<const bf16x8*>(b_in + in_off);
-      if (rope) {
+  if constexpr (sizeof(Elem) == 2) {
+    // kUnroll chunks of each tensor per lane and trip: all their loads are issued before the
+    // first is used (2 * kUnroll 16-byte loads in flight per lane), and every element is
+    // touched once, so the loads (and the append's stores) bypass the caches' keep-for-reuse policy.
+    // Measured on a plain copy of 1 GiB: 6.0 TB/s this way against 4.5 TB/s one chunk at a time.
+    // The first trip's loads are issued before the block's (cos, sin) table is built, so the
+    // fp64 sincos of the temporal pairs runs under their latency.
+    constexpr int kUnroll = 4;
+    const int n_chunks = g.gw * cpr;
+    for (int base = 0; base < n_chunks; base += kUnroll * kThreads) {
+      bf16x8 xa[kUnroll], xb[kUnroll];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float2 cs = pair_cs(tab, g, w, c * 4 + u);
-          const float a0 = (float)xa[2 * u], a1 = (float)xa[2 * u + 1];
-          xa[2 * u] = (__bf16)(a0 * cs.x - a1 * cs.y);
-          xa[2 * u + 1] = (__bf16)(a0 * cs.y + a1 * cs.x);
-          if (kRotateB) {
-            const float b0 = (float)xb[2 * u], b1 = (float)xb[2 * u + 1];
-            xb[2 * u] = (__bf16)(b0 * cs.x - b1 * cs.y);
-            xb[2 * u + 1] = (__bf16)(b0 * cs.y + b1 * cs.x);
-          }
+      for (int u = 0; u < kUnroll; ++u) {
+        const int idx = base + u * kThreads + threadIdx.x;
+        if (idx < n_chunks) {
+          const int w = idx / cpr, c = idx % cpr;
+          const int64_t in_off = ((in_tok0 + w) * g.H + h) * g.D + c * EPC;
+          xa[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(a_in + in_off));
+          xb[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(b_in + in_off));
         }
       }
-      *reinterpret_cast<bf16x8*>(a_out + out_off) = xa;
-      *reinterpret_cast<bf16x8*>(b_out + out_off) = xb;
-    } else {
+      if (rope && base == 0) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int idx = base + u * kThreads + threadIdx.x;
+        if (idx >= n_chunks) continue;
+        const int w = idx / cpr, c = idx % cpr;
+        const int64_t out_off = (out_row0 + w) * g.D + c * EPC;
+        if (rope) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float2 cs = pair_cs(tab, g, w, c * 4 + v);
+            const float a0 = (float)xa[u][2 * v], a1 = (float)xa[u][2 * v + 1];
+            xa[u][2 * v] = (__bf16)(a0 * cs.x - a1 * cs.y);
+            xa[u][2 * v + 1] = (__bf16)(a0 * cs.y + a1 * cs.x);
+            if (kRotateB) {
+              const float b0 = (float)xb[u][2 * v], b1 = (float)xb[u][2 * v + 1];
+              xb[u][2 * v] = (__bf16)(b0 * cs.x - b1 * cs.y);
+              xb[u][2 * v + 1] = (__bf16)(b0 * cs.y + b1 * cs.x);
+            }
+          }
+        }
+        if constexpr (kRotateB) {  // staged Q~, K~: read again at once by the attention launch
+          *reinterpret_cast<bf16x8*>(a_out + out_off) = xa[u];
+          *reinterpret_cast<bf16x8*>(b_out + out_off) = xb[u];
+        } else {
+          __builtin_nontemporal_store(xa[u], reinterpret_cast<bf16x8*>(a_out + out_off));
+          __builtin_nontemporal_store(xb[u], reinterpret_cast<bf16x8*>(b_out + out_off));
+        }
+      }
+    }
+    return;
+  } else {
+    // fp32 debug path: one chunk at a time
+    if (rope) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+    for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
+      const int w = idx / cpr, c = idx % cpr;
+      const int64_t in_off = ((in_tok0 + w) * g.H + h) * g.D + c * EPC;
+      const int64_t out_off = (out_row0 + w) * g.D + c * EPC;
       f32x4 xa = *reinterpret_cast<const f32x4*>(a_in + in_off);
       f32x4 xb = *reinterpret_cast<const f32x4*>(b_in + in_off);
       if (rope) {
