@@ -33,7 +33,8 @@ struct BwdParams {
   const __bf16* out;
   const __bf16* dout;
   const float* lse;
-  float* delta;   // [B][H][Nq]
+  float* delta;   // [B][H][Nq]  <dO, O>
+  float* lse2;    // [B][H][Nq]  LSE * log2(e), written next to delta by the dQ kernel
   float* dq_rot;  // [B][H][Nq][D]
   float* dk_rot;  // [B][H][Nq][D]
   float* dv;      // [B, Nq, H, D]
@@ -191,10 +192,14 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
       for (int j = 0; j < 8; ++j) dsum = fmaf((float)y[j], (float)o[j], dsum);
     }
     dsum = sum_with_partner32(dsum);
-    if (live && g == 0) p.delta[bh * p.Nq + q] = dsum;
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
     w.lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
     w.delta[qb] = dsum;
+    // the row terms of the query, for the dK/dV kernel
+    if (live && g == 0) {
+      p.delta[bh * p.Nq + q] = dsum;
+      p.lse2[bh * p.Nq + q] = w.lse2[qb];
+    }
   }
 
   const RowSegment k_hist = make_segment(p.k_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
@@ -397,38 +402,35 @@ __device__ __forceinline__ void dkv_workgroup(const BwdParams& p, int index, cha
   TileStreamer<D, QT, kWaves> ts;
   ts.init();
   const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
-  // thread < QT carries LSE*log2e of tile row `thread`, QT <= thread < 2 QT its Delta;
-  // rows past Nq get P = exp2(0 - big) = 0
-  auto rowterm = [&](int tile) {
-    const int t = threadIdx.x;
-    const int q = tile * QT + (t & (QT - 1));
-    if (t < QT) return q < p.Nq ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    return (t < 2 * QT && q < p.Nq) ? p.delta[bh * p.Nq + q] : 0.f;
-  };
+  // Row terms of a tile's queries, LSE*log2e [QT] then Delta [QT]: wave 0 and wave 1 each fetch
+  // one of the two with a direct-to-LDS load of 4 bytes per lane, so no register, branch or wait
+  // of the tile loop depends on them.  Rows past Nq read as zeros; they cannot contribute: their
+  // Q~ and dO rows are zero in LDS as well, so dP, Delta and with them dS and the dV terms are 0.
+  static_assert(QT == 64, "one 4-byte-per-lane wave load covers the QT row terms");
+  const __amdgpu_buffer_rsrc_t term_rows = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)((ts.wave == 0 ? p.lse2 : p.delta) + bh * p.Nq), 0, p.Nq * 4, 0x00020000);
+  const int term_lane = (threadIdx.x & 63) * 4;
   // tile t lives in buffer t % 2
   auto issue = [&](int t, int buf) __attribute__((always_inline)) {
+    typedef __attribute__((address_space(3))) void* lds_ptr;
     char* qbuf = lds + buf * 2 * TILE_BYTES;
     ts.issue(q_rows, off_q, t * QT, qbuf);
     ts.issue(do_rows, off_do, t * QT, qbuf + TILE_BYTES);
+    if (ts.wave < 2)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(term_rows, (lds_ptr)(rowterms + buf * 2 * QT + ts.wave * QT), 4,
+                                               t * QT * 4 + term_lane, 0, 0, 0);
   };
   issue(t_begin, t_begin & 1);
-  if (threadIdx.x < 2 * QT) rowterms[(t_begin & 1) * 2 * QT + threadIdx.x] = rowterm(t_begin);
   wait_vmem();
   __syncthreads();
 
   // two tiles per trip so that each LDS buffer is a compile-time offset of the operand reads
   auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
     constexpr int BUF = decltype(buf_c)::value;
-    const bool more = t + 1 < ntiles;
-    float rt = 0.f;
-    if (more) {
-      issue(t + 1, BUF ^ 1);
-      rt = rowterm(t + 1);
-    }
+    if (t + 1 < ntiles) issue(t + 1, BUF ^ 1);
     const char* qbuf = lds + BUF * 2 * TILE_BYTES;
     const float* terms = rowterms + BUF * 2 * QT;
     w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + QT, first_q - t * QT, first_q_wave - t * QT);
-    if (more && threadIdx.x < 2 * QT) rowterms[(BUF ^ 1) * 2 * QT + threadIdx.x] = rt;
     wait_vmem();
     __syncthreads();
   };
@@ -495,6 +497,7 @@ BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out,
   p.dout = (const __bf16*)dout;
   p.lse = lse;
   p.delta = (float*)scratch;
+  p.lse2 = p.delta + (size_t)g.B * g.H * op.Nq;
   p.dq_rot = dq_rot;
   p.dk_rot = dk_rot;
   p.dv = dv;
@@ -565,7 +568,8 @@ hipError_t launch_attn_bwd_hist_bf16(const DevGeom& g, const AttnOperands& op, c
   return launch_hist<64>(g, op, lse, dout, dk_hist_rot, dv_hist, scratch, stream);
 }
 
-size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq) { return (size_t)g.B * g.H * Nq * sizeof(float); }
+// Delta and LSE*log2e per (stream, head, query)
+size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq) { return 2 * (size_t)g.B * g.H * Nq * sizeof(float); }
 
 hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse,
                                 const void* dout, float* dq_rot, float* dk_rot, float* dv, void* scratch,
