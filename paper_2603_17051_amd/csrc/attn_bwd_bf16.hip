@@ -12,8 +12,6 @@
 // directly the B operand of the next, and the LDS tile of the other operand is read
 // either by rows (contraction over D) or through the transposing read (contraction over
 // the tile's rows).
-#include <cstdlib>
-
 #include "kernels.hpp"
 #include "mfma_common.hpp"
 
@@ -50,13 +48,13 @@ struct BwdParams {
 };
 
 // ---- dQ -----------------------------------------------------------------------
-template <int D, int NQB>
+template <int D>
 struct DqWave {
   static constexpr int QSTEPS = D / 16;
   static constexpr int DB = D / 32;
-  bf16x8 qreg[NQB][QSTEPS], doreg[NQB][QSTEPS];  // B operands: Q~ and dO rows of this lane's query
-  float lse2[NQB], delta[NQB];
-  f32x16 dq[NQB][DB];
+  bf16x8 qreg[QSTEPS], doreg[QSTEPS];  // B operands: Q~ and dO rows of this lane's query
+  float lse2, delta;
+  f32x16 dq[DB];
   OperandAddr<D> addr;
   int g;
   float scale_log2e;
@@ -66,77 +64,58 @@ struct DqWave {
     scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dq[qb][db][r] = 0.f;
+      for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
   }
 
-  // One 64-key tile of which the first `live` keys count for lane's query qb (live_min,
+  // One 64-key tile of which the first `live` keys count for this lane's query (live_min,
   // wave-uniform: the fewest over the wave).  The others lie past the end of their segment
   // (zero rows in LDS) or in a causal block the query does not see; their score is replaced
   // so that P and dS are exactly 0 (left alone, P = exp(0 - LSE) could overflow for a query
   // whose logits are all very negative, and inf * 0 would poison dQ~ = dS K~).
-  __device__ __forceinline__ void tile(const char* ks, const char* vs, const int (&live)[NQB], int live_min) {
+  // Each product reads its operand fragments just ahead of its MFMAs.  Requesting the next
+  // product's fragments one MFMA behind the current one (no product then starts by waiting for
+  // LDS) was measured slower, 5.05 vs 4.93 ms: it needs all 256 registers and the kernel is not
+  // bound by LDS latency.
+  __device__ __forceinline__ void tile(const char* ks, const char* vs, int live, int live_min) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 s[NQB], dp[NQB];
+      f32x16 s, dp;
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) {
-        const bf16x8 ak = read_rows8<D>(ks, addr.row[st], kb);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) s[qb] = mfma32(ak, qreg[qb][st], st == 0 ? zero : s[qb]);
-      }
+      for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(ks, addr.row[st], kb), qreg[st], st == 0 ? zero : s);
       if (live_min < 32 * (kb + 1)) {
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[qb][r] = 32 * kb + acc_row(r, g) >= live[qb] ? kNegBig : s[qb][r];
+        for (int r = 0; r < 16; ++r) s[r] = 32 * kb + acc_row(r, g) >= live ? kNegBig : s[r];
       }
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) {
-        const bf16x8 av = read_rows8<D>(vs, addr.row[st], kb);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) dp[qb] = mfma32(av, doreg[qb][st], st == 0 ? zero : dp[qb]);
-      }
+      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(vs, addr.row[st], kb), doreg[st], st == 0 ? zero : dp);
       __builtin_amdgcn_sched_barrier(0);
-      bf16x8 dsb[NQB][2];
+      // dS^T = P^T o (dP^T - Delta), P^T = exp2(S^T * scale*log2(e) - LSE*log2(e))
+      bf16x8 dsb[2];
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        float ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pr = fast_exp2(fmaf(s[qb][r], scale_log2e, -lse2[qb]));
-          ds[r] = pr * (dp[qb][r] - delta[qb]);
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) dsb[qb][s2][j] = (__bf16)ds[8 * s2 + j];
+      for (int r = 0; r < 16; ++r) {
+        const float pr = fast_exp2(fmaf(s[r], scale_log2e, -lse2));
+        dsb[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - delta));
       }
       __builtin_amdgcn_sched_barrier(0);
       // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
+      for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 a = read_cols8<D>(ks, addr.tr[db], 32 * kb + 16 * s2);
-#pragma unroll
-          for (int qb = 0; qb < NQB; ++qb) dq[qb][db] = mfma32(a, dsb[qb][s2], dq[qb][db]);
-        }
-      }
+        for (int db = 0; db < DB; ++db)
+          dq[db] = mfma32(read_cols8<D>(ks, addr.tr[db], 32 * kb + 16 * s2), dsb[s2], dq[db]);
     }
   }
 };
 
-template <int D, int NQB, int OCC>
+template <int D, int OCC>
 __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p) {
-  using Wave = DqWave<D, NQB>;
+  using Wave = DqWave<D>;
   constexpr int TILE_BYTES = KT * D * 2;
   __shared__ __attribute__((aligned(1024))) char lds[4 * TILE_BYTES];  // K0 V0 K1 V1
 
@@ -147,29 +126,22 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, g = lane >> 5;
   const int hist = p.hist_rows.v[pair.cache_b];
-  const int q0 = (item.tile * kWaves + wave) * 32 * NQB;
+  const int q = (item.tile * kWaves + wave) * 32 + i32;
   const int64_t bh = (int64_t)b * p.H + h;
-  // chunk rows each of this lane's queries sees, the fewest any lane of the wave sees (its
-  // first query) and the most any wave of the workgroup sees (its last query)
+  // chunk rows this lane's query sees, the fewest any lane of the wave sees (its first
+  // query) and the most any wave of the workgroup sees (its last query)
   const int q_last = p.Nq - 1;
-  int vis[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int q = q0 + 32 * qb + i32;
-    vis[qb] = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, p.block_rows);
-  }
-  const int q_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32 * NQB;
+  const int vis = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, p.block_rows);
+  const int q_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32;
   const int vis_wave = visible_chunk_rows(q_wave < q_last ? q_wave : q_last, p.Nq, p.block_rows);
-  const int q_wg = (item.tile + 1) * kWaves * 32 * NQB - 1;
+  const int q_wg = (item.tile + 1) * kWaves * 32 - 1;
   const int vis_wg = visible_chunk_rows(q_wg < q_last ? q_wg : q_last, p.Nq, p.block_rows);
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
 
   Wave w;
   w.init(lane, p.scale_log2e);
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int q = q0 + 32 * qb + i32;
+  {
     const bool live = q < p.Nq;
     const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
     const int64_t token_row = (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
@@ -186,19 +158,19 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
         y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
         o = *reinterpret_cast<const bf16x8*>(orow + st * 16 + g * 8);
       }
-      w.qreg[qb][st] = x;
-      w.doreg[qb][st] = y;
+      w.qreg[st] = x;
+      w.doreg[st] = y;
 #pragma unroll
       for (int j = 0; j < 8; ++j) dsum = fmaf((float)y[j], (float)o[j], dsum);
     }
     dsum = sum_with_partner32(dsum);
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
-    w.lse2[qb] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    w.delta[qb] = dsum;
+    w.lse2 = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    w.delta = dsum;
     // the row terms of the query, for the dK/dV kernel
     if (live && g == 0) {
       p.delta[bh * p.Nq + q] = dsum;
-      p.lse2[bh * p.Nq + q] = w.lse2[qb];
+      p.lse2[bh * p.Nq + q] = w.lse2;
     }
   }
 
@@ -228,10 +200,8 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
   auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
     if (t + 1 < ntiles) issue(t + 1);
     const char* kbuf = lds + decltype(buf_c)::value * 2 * TILE_BYTES;
-    int live[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) live[qb] = t < hist_tiles ? hist - t * KT : vis[qb] - (t - hist_tiles) * KT;
-    w.tile(kbuf, kbuf + TILE_BYTES, live, t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
+    w.tile(kbuf, kbuf + TILE_BYTES, t < hist_tiles ? hist - t * KT : vis - (t - hist_tiles) * KT,
+           t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
     wait_vmem();
     __syncthreads();
   };
@@ -240,21 +210,17 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
     if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
 
+  if (q < p.Nq) {
+    float* row = p.dq_rot + (bh * p.Nq + q) * D;
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int q = q0 + 32 * qb + i32;
-    if (q < p.Nq) {
-      float* row = p.dq_rot + (bh * p.Nq + q) * D;
+    for (int db = 0; db < Wave::DB; ++db)
 #pragma unroll
-      for (int db = 0; db < Wave::DB; ++db)
+      for (int rr = 0; rr < 4; ++rr) {
+        f32x4 x;
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          f32x4 x;
-#pragma unroll
-          for (int c = 0; c < 4; ++c) x[c] = w.dq[qb][db][4 * rr + c] * p.scale;
-          *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
-        }
-    }
+        for (int c = 0; c < 4; ++c) x[c] = w.dq[db][4 * rr + c] * p.scale;
+        *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
+      }
   }
 }
 
@@ -474,16 +440,6 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p
     dkv_workgroup<D, true, false, QT>(p, (int)blockIdx.x - n, lds);
 }
 
-// tuning knob (environment ASTRO_BWD_VARIANT): 0 = 32 queries per wave and two workgroups per
-// CU in the dQ kernel, 1 = 64 queries per wave and one workgroup per CU
-int bwd_variant() {
-  static const int v = [] {
-    const char* e = getenv("ASTRO_BWD_VARIANT");
-    return e ? atoi(e) : 0;
-  }();
-  return v;
-}
-
 template <int D>
 BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
                       float* dq_rot, float* dk_rot, float* dv, void* scratch) {
@@ -523,15 +479,9 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   BwdParams p = make_params<D>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch);
   {
     ProfileScope prof("attn_bwd_dq_bf16", stream);
-    if (bwd_variant() == 1) {
-      const int qtile = kWaves * 32 * 2;
-      p.tiles = (op.Nq + qtile - 1) / qtile;
-      attn_bwd_dq_kernel<D, 2, 1><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
-    } else {
-      const int qtile = kWaves * 32;
-      p.tiles = (op.Nq + qtile - 1) / qtile;
-      attn_bwd_dq_kernel<D, 1, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
-    }
+    const int qtile = kWaves * 32;
+    p.tiles = (op.Nq + qtile - 1) / qtile;
+    attn_bwd_dq_kernel<D, 2><<<dim3(work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
   }
   const int ktile = kWaves * 32;
   {
