@@ -333,3 +333,30 @@ def test_calibration_kernels_compute_what_their_rates_assume():
     assert torch.equal(src, dst)
     with pytest.raises(A.AstroError):
         A.astro_calib_mfma(ones, 0, 5, sink)
+
+
+@pytest.mark.parametrize("B,H,D,pairs,gh,gw,C,S,Fc,steps", [
+    (64, 1, 64, (12, 10, 10), 3, 4, 3, 1, 2, 3),      # the most streams a handle takes
+    (1, 2, 128, (22, 21, 21), 2, 3, 256, 3, 11, 26),  # the largest ring: 256 frames of 6 tokens, filled and wrapped
+])
+def test_bf16_maximum_batch_and_capacity(B, H, D, pairs, gh, gw, C, S, Fc, steps):
+    w = wl.Workload("bf16_max", 15, B, H, D, gh, gw, C, S, Fc, 0, pairs)
+    ls = Lockstep(w, start_frames=[3 * b for b in range(B)])
+    rep = []
+    for step in range(steps):
+        q, k, v, do = wl.chunk_inputs(w, step, with_dout=True)
+        if step >= steps - 2:  # the last two chunks: full ring / wrapped ring
+            out, lse = ls.fwd(q, k, v, Fc)
+            ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), Fc)
+            assert_bf16_close(host_f64(out), ro, f"step {step} out", rep)
+            assert_bf16_close(host_f64(lse), rl, f"step {step} lse", rep)
+            dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), Fc)
+            rq, rk, rv = ls.oracle.attn_bwd(ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), Fc)
+            assert_bf16_close(host_f64(dq), rq, f"step {step} dq", rep)
+            assert_bf16_close(host_f64(dk), rk, f"step {step} dk", rep)
+            assert_bf16_close(host_f64(dv), rv, f"step {step} dv", rep)
+        ls.append(k, v, Fc)
+        ls.check_tables()
+    _report(rep[-5:])
+    check_cache_contents(ls, streams=[0, B - 1])
+    ls.close()
