@@ -263,6 +263,10 @@ struct DkvWave {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       // phase order keeps few values live: S -> P -> dV products, then dP -> dS -> dK products
       f32x16 s, dp;
+      // the row terms are requested ahead of the product whose result they meet
+      f32x4 l4[4], d4[4];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) l4[rr] = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
 #pragma unroll
       for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(qs, addr.row[st], qb), kreg[st], st == 0 ? zero : s);
       if (first_max > 32 * qb) {
@@ -273,11 +277,10 @@ struct DkvWave {
       bf16x8 pb[2];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int r = 4 * rr + c;
-          s[r] = fast_exp2(fmaf(s[r], scale_log2e, -l4[c]));  // P, kept in fp32 for dS
+          s[r] = fast_exp2(fmaf(s[r], scale_log2e, -l4[rr][c]));  // P, kept in fp32 for dS
           if (DV) pb[r >> 3][r & 7] = (__bf16)s[r];
         }
       }
@@ -292,16 +295,17 @@ struct DkvWave {
       if constexpr (DK) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
+        for (int rr = 0; rr < 4; ++rr) d4[rr] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
+#pragma unroll
         for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 dsb[2];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int r = 4 * rr + c;
-            dsb[r >> 3][r & 7] = (__bf16)(s[r] * (dp[r] - d4[c]));
+            dsb[r >> 3][r & 7] = (__bf16)(s[r] * (dp[r] - d4[rr][c]));
           }
         }
         __builtin_amdgcn_sched_barrier(0);
