@@ -225,16 +225,40 @@ __global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dq_kernel(BwdParams p)
 }
 
 // ---- dK, dV of the chunk's keys ---------------------------------------------------
-// DV / DK select which of the two gradients this instantiation accumulates: computing both
-// in one wave needs more registers than two resident waves per SIMD have, so every tile of
-// keys is taken by two workgroups, one per gradient (S is recomputed in both).
-// QT = query rows per LDS tile.
-template <int D, bool DV, bool DK, int QT>
-struct DkvWave {
+// One workgroup = 8 waves = 128 keys in 4 blocks of 32 (every lane owns one key), each block
+// seen by two waves.  The "value" wave computes S = Q~ K~^T, P and dV^T += dO^T P, and hands P
+// (bf16, in the lane-private order of its accumulator registers) to its partner through LDS; the
+// "key" wave picks it up one period later and computes dP = dO V^T, dS = P o (dP - Delta) and
+// dK~^T += Q~^T dS.  Both gradients in one wave need more registers than two waves per SIMD
+// have, and two independent workgroups per key tile each compute S and the exponentials (five
+// products instead of four; that is how it was before: 1.22 ms at the 12-head, 21-frame,
+// batch-4 shape).  A query tile is used in two consecutive periods, so tiles, row terms and P
+// live in rings of three LDS slots, and a period is unrolled three times so that every slot is
+// a compile-time offset.
+constexpr int kPairWaves = 8;
+constexpr int kPairThreads = kPairWaves * 64;
+constexpr int QT = 64;  // query rows per LDS tile
+
+template <int D>
+struct DkvLds {
+  static constexpr int TILE_BYTES = QT * D * 2;
+  static constexpr int SLOT_TILES = 2 * TILE_BYTES;              // Q~ tile, dO tile
+  static constexpr int SLOT_PROBS = 4 * (QT / 32) * 2 * 1024;    // key block x query block x half: 64 lanes x 16 B
+  static constexpr int SLOT_TERMS = 2 * QT * 4;                  // LSE*log2e [QT], Delta [QT]
+  static constexpr int kProbs = 3 * SLOT_TILES;
+  static constexpr int kTerms = kProbs + 3 * SLOT_PROBS;
+  static constexpr int kTotal = kTerms + 3 * SLOT_TERMS;
+  static_assert(kTotal <= 160 * 1024, "one workgroup per CU must fit the LDS");
+};
+
+// Tile rows below `first` (per lane; first_max, wave-uniform, = the largest over the wave) are
+// queries of an earlier causal block than this lane's key: they do not see it, P = 0.
+template <int D>
+struct ValueWave {
   static constexpr int QSTEPS = D / 16;
   static constexpr int DB = D / 32;
-  bf16x8 kreg[QSTEPS], vreg[DK ? QSTEPS : 1];  // B operands: K~ and V rows of this lane's chunk key
-  f32x16 dk[DK ? DB : 1], dv[DV ? DB : 1];
+  bf16x8 kreg[QSTEPS];  // B operand: K~ row of this lane's key
+  f32x16 dv[DB];
   OperandAddr<D> addr;
   int g;
   float scale_log2e;
@@ -246,25 +270,19 @@ struct DkvWave {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (DK) dk[db][r] = 0.f;
-        if (DV) dv[db][r] = 0.f;
-      }
+      for (int r = 0; r < 16; ++r) dv[db][r] = 0.f;
   }
 
-  // One tile of QT queries: qs / dos = Q~ and dO tiles, lse_t / delta_t = their row terms.
-  // Tile rows below `first` (per lane; first_max, wave-uniform, = the largest over the wave)
-  // are queries of an earlier causal block than this lane's key: they do not see it, P = 0.
-  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, const float* delta_t,
-                                       int first, int first_max) {
+  // qs / dos = Q~ and dO tiles, lse_t = LSE*log2e of the tile's rows, probs = this wave's part of a P slot
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs, int first,
+                                       int first_max) {
 #pragma unroll
     for (int qb = 0; qb < QT / 32; ++qb) {
-      // S[q][key] and dP[q][key]: rows = 32 queries of the tile, column = this lane's key
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      // phase order keeps few values live: S -> P -> dV products, then dP -> dS -> dK products
-      f32x16 s, dp;
-      // the row terms are requested ahead of the product whose result they meet
-      f32x4 l4[4], d4[4];
+      // S[q][key]: rows = 32 queries of the tile, column = this lane's key; the row terms are
+      // requested ahead of the product whose result they meet
+      f32x16 s;
+      f32x4 l4[4];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) l4[rr] = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
 #pragma unroll
@@ -276,67 +294,80 @@ struct DkvWave {
       __builtin_amdgcn_sched_barrier(0);
       bf16x8 pb[2];
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int r = 4 * rr + c;
-          s[r] = fast_exp2(fmaf(s[r], scale_log2e, -l4[rr][c]));  // P, kept in fp32 for dS
-          if (DV) pb[r >> 3][r & 7] = (__bf16)s[r];
-        }
-      }
+      for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, -l4[r >> 2][r & 3]));
+      *reinterpret_cast<bf16x8*>(probs + (2 * qb) * 1024) = pb[0];
+      *reinterpret_cast<bf16x8*>(probs + (2 * qb + 1) * 1024) = pb[1];
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (DV) {
-        // dV^T[d][key] += dO^T[d][q] P[q][key]
+      // dV^T[d][key] += dO^T[d][q] P[q][key]
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
+      for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-          for (int db = 0; db < DB; ++db) dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
-      }
-      if constexpr (DK) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) d4[rr] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
-#pragma unroll
-        for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 dsb[2];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int r = 4 * rr + c;
-            dsb[r >> 3][r & 7] = (__bf16)(s[r] * (dp[r] - d4[rr][c]));
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int db = 0; db < DB; ++db) dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
-      }
+        for (int db = 0; db < DB; ++db) dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
     }
   }
 };
 
-// Work of one workgroup, number `index` among those that accumulate this gradient.
-// lds: 4 * QT * D * 2 + 4 * QT * 4 bytes -- Q0 dO0 Q1 dO1 tiles, then per-buffer LSE*log2e [QT] and Delta [QT].
-template <int D, bool DV, bool DK, int QT>
-__device__ __forceinline__ void dkv_workgroup(const BwdParams& p, int index, char* lds) {
-  using Wave = DkvWave<D, DV, DK, QT>;
-  constexpr int TILE_BYTES = QT * D * 2;
-  float* rowterms = reinterpret_cast<float*>(lds + 4 * TILE_BYTES);
+template <int D>
+struct KeyWave {
+  static constexpr int QSTEPS = D / 16;
+  static constexpr int DB = D / 32;
+  bf16x8 vreg[QSTEPS];  // B operand: V row of this lane's key
+  f32x16 dk[DB];
+  OperandAddr<D> addr;
+  int g;
 
-  const WorkItem item = work_item(p.tiles, p.BH, false, index);
-  if (!item.valid) return;
+  __device__ __forceinline__ void init(int lane) {
+    g = lane >> 5;
+    addr.init(lane);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dk[db][r] = 0.f;
+  }
+
+  // qs / dos = Q~ and dO tiles, delta_t = Delta of the tile's rows, probs = the partner's P of this tile
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* delta_t, const char* probs) {
+#pragma unroll
+    for (int qb = 0; qb < QT / 32; ++qb) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 dp;
+      f32x4 d4[4];
+      bf16x8 pb[2];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) d4[rr] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
+      pb[0] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb) * 1024);
+      pb[1] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb + 1) * 1024);
+      // dP[q][key] = <dO_q, V_key>
+#pragma unroll
+      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 dsb[2];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dsb[r >> 3][r & 7] = (__bf16)((float)pb[r >> 3][r & 7] * (dp[r] - d4[r >> 2][r & 3]));
+      __builtin_amdgcn_sched_barrier(0);
+      // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
+    }
+  }
+};
+
+// Everything one wave does, in its role (kKey: a key wave, else a value wave).  Both roles
+// stream the tiles and meet at the same barriers, one per period.
+template <int D, bool kKey>
+__device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& item, int wave, char* lds) {
+  using L = DkvLds<D>;
+  using Wave = std::conditional_t<kKey, KeyWave<D>, ValueWave<D>>;
   const int b = item.bh / p.H, h = item.bh % p.H;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int kw = wave & 3;  // key block of the workgroup's four
   const int i32 = lane & 31, g = lane >> 5;
   const int64_t bh = (int64_t)b * p.H + h;
   // this lane's key: a chunk row, or (non-detached backward) a resident ring row of the stream
   const int n_keys = p.hist_keys ? p.hist_rows.v[b] : p.Nq;
-  if (item.tile * kWaves * 32 >= n_keys) return;  // whole workgroup, before any barrier
-  const int jc = (item.tile * kWaves + wave) * 32 + i32;
+  const int jc = (item.tile * 4 + kw) * 32 + i32;
   const bool live = jc < n_keys;
   const int ntiles = (p.Nq + QT - 1) / QT;
   // first query row that sees this lane's key (ring rows are seen by every query), the
@@ -344,104 +375,126 @@ __device__ __forceinline__ void dkv_workgroup(const BwdParams& p, int index, cha
   const int block_rows = p.hist_keys ? 0 : p.block_rows;
   const int j_last = n_keys - 1;
   const int first_q = first_query_row_seeing(jc < j_last ? jc : j_last, block_rows);
-  const int j_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32 + 31;
+  const int j_wave = (item.tile * 4 + kw) * 32 + 31;
   const int first_q_wave = first_query_row_seeing(j_wave < j_last ? j_wave : j_last, block_rows);
-  const int t_begin = first_query_row_seeing(item.tile * kWaves * 32, block_rows) / QT;
+  const int t_begin = first_query_row_seeing(item.tile * 128, block_rows) / QT;
 
   Wave w;
-  w.init(lane, p.scale_log2e);
+  if constexpr (kKey)
+    w.init(lane);
+  else
+    w.init(lane, p.scale_log2e);
   {
+    // B operand of the role's first product: V row (key wave) or K~ row (value wave) of the lane's key
     const int j0 = live ? jc : 0;
-    const __bf16* krow = p.hist_keys ? p.k_cache + (bh * p.cache_rows + j0) * D : p.kc_rot + (bh * p.Nq + j0) * D;
-    const __bf16* vrow = p.hist_keys ? p.v_cache + (bh * p.cache_rows + j0) * D
-                                     : p.v_chunk + (((int64_t)b * p.Nq + j0) * p.H + h) * D;
+    const __bf16* row;
+    if constexpr (kKey)
+      row = p.hist_keys ? p.v_cache + (bh * p.cache_rows + j0) * D : p.v_chunk + (((int64_t)b * p.Nq + j0) * p.H + h) * D;
+    else
+      row = p.hist_keys ? p.k_cache + (bh * p.cache_rows + j0) * D : p.kc_rot + (bh * p.Nq + j0) * D;
 #pragma unroll
-    for (int st = 0; st < Wave::QSTEPS; ++st) {
-      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x;
-      if (live) {
-        x = *reinterpret_cast<const bf16x8*>(krow + st * 16 + g * 8);
-        y = *reinterpret_cast<const bf16x8*>(vrow + st * 16 + g * 8);
-      }
-      w.kreg[st] = x;
-      if (DK) w.vreg[st] = y;
+    for (int st = 0; st < D / 16; ++st) {
+      bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (live) x = *reinterpret_cast<const bf16x8*>(row + st * 16 + g * 8);
+      if constexpr (kKey)
+        w.vreg[st] = x;
+      else
+        w.kreg[st] = x;
     }
   }
 
   const RowSegment q_rows = make_segment(p.q_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment do_rows = make_segment(p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, QT, kWaves> ts;
+  TileStreamer<D, QT, kPairWaves> ts;
   ts.init();
   const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
-  // Row terms of a tile's queries, LSE*log2e [QT] then Delta [QT]: wave 0 and wave 1 each fetch
-  // one of the two with a direct-to-LDS load of 4 bytes per lane, so no register, branch or wait
-  // of the tile loop depends on them.  Rows past Nq read as zeros; they cannot contribute: their
-  // Q~ and dO rows are zero in LDS as well, so dP, Delta and with them dS and the dV terms are 0.
-  static_assert(QT == 64, "one 4-byte-per-lane wave load covers the QT row terms");
+  // Row terms of a tile's queries: wave 0 fetches LSE*log2e and wave 1 Delta with a direct-to-LDS
+  // load of 4 bytes per lane, so no register, branch or wait of the tile loop depends on them.
+  // Rows past Nq read as zeros; they cannot contribute: their Q~ and dO rows are zero in LDS as
+  // well, so dP, Delta and with them dS and the dV terms are 0.
   const __amdgpu_buffer_rsrc_t term_rows = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((ts.wave == 0 ? p.lse2 : p.delta) + bh * p.Nq), 0, p.Nq * 4, 0x00020000);
-  const int term_lane = (threadIdx.x & 63) * 4;
-  // tile t lives in buffer t % 2
-  auto issue = [&](int t, int buf) __attribute__((always_inline)) {
+      (void*)((wave == 0 ? p.lse2 : p.delta) + bh * p.Nq), 0, p.Nq * 4, 0x00020000);
+  const int term_lane = lane * 4;
+  auto issue = [&](int t, int slot) __attribute__((always_inline)) {
     typedef __attribute__((address_space(3))) void* lds_ptr;
-    char* qbuf = lds + buf * 2 * TILE_BYTES;
+    char* qbuf = lds + slot * L::SLOT_TILES;
     ts.issue(q_rows, off_q, t * QT, qbuf);
-    ts.issue(do_rows, off_do, t * QT, qbuf + TILE_BYTES);
-    if (ts.wave < 2)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(term_rows, (lds_ptr)(rowterms + buf * 2 * QT + ts.wave * QT), 4,
-                                               t * QT * 4 + term_lane, 0, 0, 0);
+    ts.issue(do_rows, off_do, t * QT, qbuf + L::TILE_BYTES);
+    if (!kKey && wave < 2)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(term_rows, (lds_ptr)(lds + L::kTerms + slot * L::SLOT_TERMS + wave * QT * 4),
+                                               4, t * QT * 4 + term_lane, 0, 0, 0);
   };
-  issue(t_begin, t_begin & 1);
+  issue(t_begin, 0);
   wait_vmem();
   __syncthreads();
 
-  // two tiles per trip so that each LDS buffer is a compile-time offset of the operand reads
-  auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
-    constexpr int BUF = decltype(buf_c)::value;
-    if (t + 1 < ntiles) issue(t + 1, BUF ^ 1);
-    const char* qbuf = lds + BUF * 2 * TILE_BYTES;
-    const float* terms = rowterms + BUF * 2 * QT;
-    w.tile(qbuf, qbuf + TILE_BYTES, terms, terms + QT, first_q - t * QT, first_q_wave - t * QT);
+  // Period n: the value waves work on tile n (slot S), the key waves on tile n - 1 (slot S - 1),
+  // tile n + 1 streams into slot S + 1; the last period has only the key waves' tile left.
+  const int probs_lane = kw * (QT / 32) * 2 * 1024 + lane * 16;
+  auto period = [&](int n, auto slot_c) __attribute__((always_inline)) {
+    constexpr int S = decltype(slot_c)::value, PREV = (S + 2) % 3, NEXT = (S + 1) % 3;
+    if (n + 1 < ntiles) issue(n + 1, NEXT);
+    if constexpr (kKey) {
+      if (n > t_begin)
+        w.tile(lds + PREV * L::SLOT_TILES, lds + PREV * L::SLOT_TILES + L::TILE_BYTES,
+               reinterpret_cast<const float*>(lds + L::kTerms + PREV * L::SLOT_TERMS) + QT,
+               lds + L::kProbs + PREV * L::SLOT_PROBS + probs_lane);
+    } else {
+      if (n < ntiles)
+        w.tile(lds + S * L::SLOT_TILES, lds + S * L::SLOT_TILES + L::TILE_BYTES,
+               reinterpret_cast<const float*>(lds + L::kTerms + S * L::SLOT_TERMS),
+               lds + L::kProbs + S * L::SLOT_PROBS + probs_lane, first_q - n * QT, first_q_wave - n * QT);
+    }
     wait_vmem();
     __syncthreads();
   };
-  int t = t_begin;
-  if (t & 1) step(t++, std::integral_constant<int, 1>{});
-  for (; t < ntiles; t += 2) {
-    step(t, std::integral_constant<int, 0>{});
-    if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
+  for (int n = t_begin;;) {
+    period(n, std::integral_constant<int, 0>{});
+    if (++n > ntiles) break;
+    period(n, std::integral_constant<int, 1>{});
+    if (++n > ntiles) break;
+    period(n, std::integral_constant<int, 2>{});
+    if (++n > ntiles) break;
   }
 
   if (live) {
-    float* krow = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + jc) * D : p.dk_rot + (bh * p.Nq + jc) * D;
-    float* vrow = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + jc) * p.H + h) * D
-                              : p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
+    float* row;
+    if constexpr (kKey)
+      row = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + jc) * D : p.dk_rot + (bh * p.Nq + jc) * D;
+    else
+      row = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + jc) * p.H + h) * D
+                        : p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
 #pragma unroll
-    for (int db = 0; db < Wave::DB; ++db)
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        f32x4 wk, wv;
+        f32x4 x;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          if (DK) wk[c] = w.dk[db][4 * rr + c] * p.scale;
-          if (DV) wv[c] = w.dv[db][4 * rr + c];
+          if constexpr (kKey)
+            x[c] = w.dk[db][4 * rr + c] * p.scale;
+          else
+            x[c] = w.dv[db][4 * rr + c];
         }
-        if (DK) *reinterpret_cast<f32x4*>(krow + 32 * db + 8 * rr + 4 * g) = wk;
-        if (DV) *reinterpret_cast<f32x4*>(vrow + 32 * db + 8 * rr + 4 * g) = wv;
+        *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
       }
   }
 }
 
-// One launch for both gradients: the first tiles * BH workgroups accumulate dK (the longer
-// job: S, dP, dK), the rest dV (S, dV), so the two kinds fill the chip together instead of
-// each ending in its own partly filled round of workgroups.
-template <int D, int OCC, int QT>
-__global__ void __launch_bounds__(kThreads, OCC) attn_bwd_dkv_kernel(BwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds[4 * QT * D * 2 + 4 * QT * 4];
-  const int n = p.tiles * p.BH;
-  if ((int)blockIdx.x < n)
-    dkv_workgroup<D, false, true, QT>(p, (int)blockIdx.x, lds);
+template <int D>
+__global__ void __launch_bounds__(kPairThreads, 1) attn_bwd_dkv_kernel(BwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[DkvLds<D>::kTotal];
+  const WorkItem item = work_item(p.tiles, p.BH, false);
+  if (!item.valid) return;
+  const int n_keys = p.hist_keys ? p.hist_rows.v[item.bh / p.H] : p.Nq;
+  if (item.tile * 128 >= n_keys) return;  // whole workgroup, before any barrier
+  // waves 0..3 accumulate dV, waves 4..7 dK; the branch is per wave, and both sides execute
+  // the same sequence of barriers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave >= 4)
+    dkv_wave<D, true>(p, item, wave, lds);
   else
-    dkv_workgroup<D, true, false, QT>(p, (int)blockIdx.x - n, lds);
+    dkv_wave<D, false>(p, item, wave, lds);
 }
 
 template <int D>
@@ -491,7 +544,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, con
   {
     ProfileScope prof("attn_bwd_dkv_bf16", stream);
     p.tiles = (op.Nq + ktile - 1) / ktile;
-    attn_bwd_dkv_kernel<D, 2, 64><<<dim3(2 * work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+    attn_bwd_dkv_kernel<D><<<dim3(work_grid_size(p.tiles, p.BH)), kPairThreads, 0, stream>>>(p);
   }
   return hipGetLastError();
 }
@@ -509,7 +562,7 @@ hipError_t launch_hist(const DevGeom& g, const AttnOperands& op, const float* ls
   const int ktile = kWaves * 32;
   p.tiles = (max_hist + ktile - 1) / ktile;
   ProfileScope prof("attn_bwd_dkv_hist_bf16", stream);
-  attn_bwd_dkv_kernel<D, 2, 64><<<dim3(2 * work_grid_size(p.tiles, p.BH)), kThreads, 0, stream>>>(p);
+  attn_bwd_dkv_kernel<D><<<dim3(work_grid_size(p.tiles, p.BH)), kPairThreads, 0, stream>>>(p);
   return hipGetLastError();
 }
 
