@@ -49,67 +49,93 @@ struct BwdParams {
 };
 
 // ---- dQ -----------------------------------------------------------------------
+// 16x16x32 MFMAs: a wave's 32 queries are two sub-blocks of 16 (qs); lane (i = lane % 16,
+// g = lane / 16) holds, for queries 16*qs + i, the accumulator rows 4g .. 4g+3 of every 16-row tile.
 template <int D>
 struct DqWave {
-  static constexpr int QSTEPS = D / 16;
-  static constexpr int DB = D / 32;
-  bf16x8 qreg[QSTEPS], doreg[QSTEPS];  // B operands: Q~ and dO rows of this lane's query
-  float lse2, delta;
-  f32x16 dq[DB];
-  OperandAddr<D> addr;
+  static constexpr int KS = D / 32;  // k-steps of a contraction over D
+  static constexpr int DT = D / 16;  // 16-row tiles of dQ~^T
+  bf16x8 qreg[2][KS], doreg[2][KS];  // B operands: Q~ and dO rows of this lane's two queries
+  float lse2[2], delta[2];
+  f32x4 dq[DT][2];
+  OperandAddr16<D> addr;
   int g;
   float scale_log2e;
 
   __device__ __forceinline__ void init(int lane, float sl2e) {
-    g = lane >> 5;
+    g = lane >> 4;
     scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
+      for (int qs = 0; qs < 2; ++qs) dq[dt][qs] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // One 64-key tile of which the first `live` keys count for this lane's query (live_min,
+  // One 64-key tile of which the first live[qs] keys count for this lane's query qs (live_min,
   // wave-uniform: the fewest over the wave).  The others lie past the end of their segment
   // (zero rows in LDS) or in a causal block the query does not see; their score is replaced
   // so that P and dS are exactly 0 (left alone, P = exp(0 - LSE) could overflow for a query
   // whose logits are all very negative, and inf * 0 would poison dQ~ = dS K~).
   // Each product reads its operand fragments just ahead of its MFMAs.  Requesting the next
   // product's fragments one MFMA behind the current one (no product then starts by waiting for
-  // LDS) was measured slower, 5.05 vs 4.93 ms: it needs all 256 registers and the kernel is not
-  // bound by LDS latency.
-  __device__ __forceinline__ void tile(const char* ks, const char* vs, int live, int live_min) {
+  // LDS) was measured slower with the 32x32x16 kernel, 5.05 vs 4.93 ms: it needs all 256
+  // registers and the kernel is not bound by LDS latency.
+  __device__ __forceinline__ void tile(const char* ks, const char* vs, const int (&live)[2], int live_min) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 s, dp;
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      f32x4 s[2][2], dp[2][2];  // [16-key half][query sub-block]
+      // S^T = K Q~^T
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(ks, addr.row[st], kb), qreg[st], st == 0 ? zero : s);
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+          const bf16x8 a = read_rows16<D>(ks, addr.row[st], 32 * kb + 16 * kh);
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs) s[kh][qs] = mfma16(a, qreg[qs][st], st == 0 ? zero : s[kh][qs]);
+        }
       if (live_min < 32 * (kb + 1)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 32 * kb + acc_row(r, g) >= live ? kNegBig : s[r];
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[kh][qs][r] = 32 * kb + 16 * kh + 4 * g + r >= live[qs] ? kNegBig : s[kh][qs][r];
       }
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
       __builtin_amdgcn_sched_barrier(0);
+      // dP^T = V dO^T
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(vs, addr.row[st], kb), doreg[st], st == 0 ? zero : dp);
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+          const bf16x8 a = read_rows16<D>(vs, addr.row[st], 32 * kb + 16 * kh);
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs) dp[kh][qs] = mfma16(a, doreg[qs][st], st == 0 ? zero : dp[kh][qs]);
+        }
       __builtin_amdgcn_sched_barrier(0);
-      // dS^T = P^T o (dP^T - Delta), P^T = exp2(S^T * scale*log2(e) - LSE*log2(e))
+      // dS^T = P^T o (dP^T - Delta), P^T = exp2(S^T * scale*log2(e) - LSE*log2(e)); as the B operand
+      // of the next product: k-slots 8g .. 8g+3 <- keys 4g .., k-slots 8g+4 .. <- keys 16 + 4g ..
       bf16x8 dsb[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pr = fast_exp2(fmaf(s[r], scale_log2e, -lse2));
-        dsb[r >> 3][r & 7] = (__bf16)(pr * (dp[r] - delta));
-      }
+      for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float pr = fast_exp2(fmaf(s[kh][qs][r], scale_log2e, -lse2[qs]));
+            dsb[qs][4 * kh + r] = (__bf16)(pr * (dp[kh][qs][r] - delta[qs]));
+          }
       __builtin_amdgcn_sched_barrier(0);
       // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8 a = read_cols16<D>(ks, addr.tr[dt], 32 * kb);
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-          dq[db] = mfma32(read_cols8<D>(ks, addr.tr[db], 32 * kb + 16 * s2), dsb[s2], dq[db]);
+        for (int qs = 0; qs < 2; ++qs) dq[dt][qs] = mfma16(a, dsb[qs], dq[dt][qs]);
+      }
     }
   }
 };
@@ -125,14 +151,16 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
   const PairIndex pair = split_pair(item.bh, p.H, p.group);
   const int b = pair.b, h = pair.h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i32 = lane & 31, g = lane >> 5;
+  const int i16 = lane & 15, g = lane >> 4;
   const int hist = p.hist_rows.v[pair.cache_b];
-  const int q = (item.tile * kWaves + wave) * 32 + i32;
+  const int q0 = (item.tile * kWaves + wave) * 32 + i16;  // this lane's queries: q0 and q0 + 16
   const int64_t bh = (int64_t)b * p.H + h;
-  // chunk rows this lane's query sees, the fewest any lane of the wave sees (its first
-  // query) and the most any wave of the workgroup sees (its last query)
+  // chunk rows each of this lane's queries sees, the fewest any lane of the wave sees (its
+  // first query) and the most any wave of the workgroup sees (its last query)
   const int q_last = p.Nq - 1;
-  const int vis = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, p.block_rows);
+  int vis[2];
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) vis[qs] = visible_chunk_rows(q0 + 16 * qs < q_last ? q0 + 16 * qs : q_last, p.Nq, p.block_rows);
   const int q_wave = (item.tile * kWaves + __builtin_amdgcn_readfirstlane(wave)) * 32;
   const int vis_wave = visible_chunk_rows(q_wave < q_last ? q_wave : q_last, p.Nq, p.block_rows);
   const int q_wg = (item.tile + 1) * kWaves * 32 - 1;
@@ -142,36 +170,39 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
 
   Wave w;
   w.init(lane, p.scale_log2e);
-  {
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    const int q = q0 + 16 * qs;
     const bool live = q < p.Nq;
     const __bf16* qrow = p.q_rot + (bh * p.Nq + (live ? q : 0)) * D;
     const int64_t token_row = (((int64_t)b * p.Nq + (live ? q : 0)) * p.H + h) * D;
     const __bf16* drow = p.dout + token_row;
     const __bf16* orow = p.out + token_row;
-    // Delta = <dO_q, O_q>: this lane holds the halves 16*st + 8g .. +7 of the row, its
-    // partner lane the others
+    // Delta = <dO_q, O_q>: this lane holds the quarter 32*st + 8g .. +7 of the row, the lanes
+    // i + 16, i + 32, i + 48 the others
     float dsum = 0.f;
 #pragma unroll
-    for (int st = 0; st < Wave::QSTEPS; ++st) {
+    for (int st = 0; st < Wave::KS; ++st) {
       bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0}, y = x, o = x;
       if (live) {
-        x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
-        y = *reinterpret_cast<const bf16x8*>(drow + st * 16 + g * 8);
-        o = *reinterpret_cast<const bf16x8*>(orow + st * 16 + g * 8);
+        x = *reinterpret_cast<const bf16x8*>(qrow + st * 32 + g * 8);
+        y = *reinterpret_cast<const bf16x8*>(drow + st * 32 + g * 8);
+        o = *reinterpret_cast<const bf16x8*>(orow + st * 32 + g * 8);
       }
-      w.qreg[st] = x;
-      w.doreg[st] = y;
+      w.qreg[qs][st] = x;
+      w.doreg[qs][st] = y;
 #pragma unroll
       for (int j = 0; j < 8; ++j) dsum = fmaf((float)y[j], (float)o[j], dsum);
     }
-    dsum = sum_with_partner32(dsum);
+    dsum += __shfl_xor(dsum, 16);
+    dsum += __shfl_xor(dsum, 32);
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
-    w.lse2 = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    w.delta = dsum;
+    w.lse2[qs] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
+    w.delta[qs] = dsum;
     // the row terms of the query, for the dK/dV kernel
     if (live && g == 0) {
       p.delta[bh * p.Nq + q] = dsum;
-      p.lse2[bh * p.Nq + q] = w.lse2;
+      p.lse2[bh * p.Nq + q] = w.lse2[qs];
     }
   }
 
@@ -179,7 +210,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
   const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, KT, kWaves> ts;
+  TileStreamer<D, KT, kWaves, true> ts;
   ts.init();
   const uint32_t off_dense = ts.lane_offset(k_hist);
   const uint32_t off_vchunk = ts.lane_offset(v_chunk);
@@ -201,8 +232,10 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
   auto step = [&](int t, auto buf_c) __attribute__((always_inline)) {
     if (t + 1 < ntiles) issue(t + 1);
     const char* kbuf = lds + decltype(buf_c)::value * 2 * TILE_BYTES;
-    w.tile(kbuf, kbuf + TILE_BYTES, t < hist_tiles ? hist - t * KT : vis - (t - hist_tiles) * KT,
-           t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
+    int live[2];
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) live[qs] = t < hist_tiles ? hist - t * KT : vis[qs] - (t - hist_tiles) * KT;
+    w.tile(kbuf, kbuf + TILE_BYTES, live, t < hist_tiles ? hist - t * KT : vis_wave - (t - hist_tiles) * KT);
     wait_vmem();
     __syncthreads();
   };
@@ -211,17 +244,19 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
     if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
 
-  if (q < p.Nq) {
-    float* row = p.dq_rot + (bh * p.Nq + q) * D;
 #pragma unroll
-    for (int db = 0; db < Wave::DB; ++db)
+  for (int qs = 0; qs < 2; ++qs) {
+    const int q = q0 + 16 * qs;
+    if (q < p.Nq) {
+      float* row = p.dq_rot + (bh * p.Nq + q) * D;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
+      for (int dt = 0; dt < Wave::DT; ++dt) {
         f32x4 x;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) x[c] = w.dq[db][4 * rr + c] * p.scale;
-        *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
+        for (int c = 0; c < 4; ++c) x[c] = w.dq[dt][qs][c] * p.scale;
+        *reinterpret_cast<f32x4*>(row + 16 * dt + 4 * g) = x;
       }
+    }
   }
 }
 
