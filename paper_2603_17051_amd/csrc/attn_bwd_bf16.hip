@@ -287,105 +287,135 @@ struct DkvLds {
   static_assert(kTotal <= 160 * 1024, "one workgroup per CU must fit the LDS");
 };
 
-// Tile rows below `first` (per lane; first_max, wave-uniform, = the largest over the wave) are
-// queries of an earlier causal block than this lane's key: they do not see it, P = 0.
+// 16x16x32 MFMAs: a wave's 32 keys are two sub-blocks of 16 (ks); lane (i = lane % 16,
+// g = lane / 16) holds, for keys 16*ks + i, the accumulator rows 4g .. 4g+3 of every 16-row tile.
+// Tile rows below first[ks] (per lane; first_max, wave-uniform, = the largest over the wave) are
+// queries of an earlier causal block than the lane's key ks: they do not see it, P = 0.
 template <int D>
 struct ValueWave {
-  static constexpr int QSTEPS = D / 16;
-  static constexpr int DB = D / 32;
-  bf16x8 kreg[QSTEPS];  // B operand: K~ row of this lane's key
-  f32x16 dv[DB];
-  OperandAddr<D> addr;
+  static constexpr int KS = D / 32;  // k-steps of a contraction over D
+  static constexpr int DT = D / 16;  // 16-row tiles of dV^T
+  bf16x8 kreg[2][KS];  // B operand: K~ rows of this lane's two keys
+  f32x4 dv[DT][2];
+  OperandAddr16<D> addr;
   int g;
   float scale_log2e;
 
   __device__ __forceinline__ void init(int lane, float sl2e) {
-    g = lane >> 5;
+    g = lane >> 4;
     scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dv[db][r] = 0.f;
+      for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   // qs / dos = Q~ and dO tiles, lse_t = LSE*log2e of the tile's rows, probs = this wave's part of a P slot
-  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs, int first,
-                                       int first_max) {
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs,
+                                       const int (&first)[2], int first_max) {
 #pragma unroll
     for (int qb = 0; qb < QT / 32; ++qb) {
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      // S[q][key]: rows = 32 queries of the tile, column = this lane's key; the row terms are
-      // requested ahead of the product whose result they meet
-      f32x16 s;
-      f32x4 l4[4];
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      // S[q][key]: rows = 32 queries of the tile in two halves of 16 (qh), column = the lane's key
+      // ks; the row terms are requested ahead of the product whose result they meet
+      f32x4 s[2][2], l4[2];
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) l4[rr] = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 8 * rr + 4 * g);
+      for (int qh = 0; qh < 2; ++qh) l4[qh] = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 16 * qh + 4 * g);
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) s = mfma32(read_rows8<D>(qs, addr.row[st], qb), kreg[st], st == 0 ? zero : s);
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int qh = 0; qh < 2; ++qh) {
+          const bf16x8 a = read_rows16<D>(qs, addr.row[st], 32 * qb + 16 * qh);
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) s[qh][ks] = mfma16(a, kreg[ks][st], st == 0 ? zero : s[qh][ks]);
+        }
       if (first_max > 32 * qb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 32 * qb + acc_row(r, g) < first ? kNegBig : s[r];
+        for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[qh][ks][r] = 32 * qb + 16 * qh + 4 * g + r < first[ks] ? kNegBig : s[qh][ks][r];
       }
       __builtin_amdgcn_sched_barrier(0);
+      // P as the B operand of the next product: k-slots 8g .. 8g+3 <- queries 4g .., 8g+4 .. <- queries 16 + 4g ..
       bf16x8 pb[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, -l4[r >> 2][r & 3]));
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pb[ks][4 * qh + r] = (__bf16)fast_exp2(fmaf(s[qh][ks][r], scale_log2e, -l4[qh][r]));
       *reinterpret_cast<bf16x8*>(probs + (2 * qb) * 1024) = pb[0];
       *reinterpret_cast<bf16x8*>(probs + (2 * qb + 1) * 1024) = pb[1];
       __builtin_amdgcn_sched_barrier(0);
       // dV^T[d][key] += dO^T[d][q] P[q][key]
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8 a = read_cols16<D>(dos, addr.tr[dt], 32 * qb);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) dv[db] = mfma32(read_cols8<D>(dos, addr.tr[db], 32 * qb + 16 * s2), pb[s2], dv[db]);
+        for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = mfma16(a, pb[ks], dv[dt][ks]);
+      }
     }
   }
 };
 
 template <int D>
 struct KeyWave {
-  static constexpr int QSTEPS = D / 16;
-  static constexpr int DB = D / 32;
-  bf16x8 vreg[QSTEPS];  // B operand: V row of this lane's key
-  f32x16 dk[DB];
-  OperandAddr<D> addr;
+  static constexpr int KS = D / 32;
+  static constexpr int DT = D / 16;
+  bf16x8 vreg[2][KS];  // B operand: V rows of this lane's two keys
+  f32x4 dk[DT][2];
+  OperandAddr16<D> addr;
   int g;
 
   __device__ __forceinline__ void init(int lane) {
-    g = lane >> 5;
+    g = lane >> 4;
     addr.init(lane);
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dk[db][r] = 0.f;
+      for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   // qs / dos = Q~ and dO tiles, delta_t = Delta of the tile's rows, probs = the partner's P of this tile
   __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* delta_t, const char* probs) {
 #pragma unroll
     for (int qb = 0; qb < QT / 32; ++qb) {
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 dp;
-      f32x4 d4[4];
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      f32x4 dp[2][2], d4[2];
       bf16x8 pb[2];
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) d4[rr] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 8 * rr + 4 * g);
+      for (int qh = 0; qh < 2; ++qh) d4[qh] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 16 * qh + 4 * g);
       pb[0] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb) * 1024);
       pb[1] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb + 1) * 1024);
       // dP[q][key] = <dO_q, V_key>
 #pragma unroll
-      for (int st = 0; st < QSTEPS; ++st) dp = mfma32(read_rows8<D>(dos, addr.row[st], qb), vreg[st], st == 0 ? zero : dp);
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int qh = 0; qh < 2; ++qh) {
+          const bf16x8 a = read_rows16<D>(dos, addr.row[st], 32 * qb + 16 * qh);
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) dp[qh][ks] = mfma16(a, vreg[ks][st], st == 0 ? zero : dp[qh][ks]);
+        }
       __builtin_amdgcn_sched_barrier(0);
       bf16x8 dsb[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dsb[r >> 3][r & 7] = (__bf16)((float)pb[r >> 3][r & 7] * (dp[r] - d4[r >> 2][r & 3]));
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            dsb[ks][4 * qh + r] = (__bf16)((float)pb[ks][4 * qh + r] * (dp[qh][ks][r] - d4[qh][r]));
       __builtin_amdgcn_sched_barrier(0);
       // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8 a = read_cols16<D>(qs, addr.tr[dt], 32 * qb);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) dk[db] = mfma32(read_cols8<D>(qs, addr.tr[db], 32 * qb + 16 * s2), dsb[s2], dk[db]);
+        for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = mfma16(a, dsb[ks], dk[dt][ks]);
+      }
     }
   }
 };
@@ -399,18 +429,19 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
   const int b = item.bh / p.H, h = item.bh % p.H;
   const int lane = threadIdx.x & 63;
   const int kw = wave & 3;  // key block of the workgroup's four
-  const int i32 = lane & 31, g = lane >> 5;
+  const int i16 = lane & 15, g = lane >> 4;
   const int64_t bh = (int64_t)b * p.H + h;
-  // this lane's key: a chunk row, or (non-detached backward) a resident ring row of the stream
+  // this lane's two keys jc and jc + 16: chunk rows, or (non-detached backward) resident ring rows of the stream
   const int n_keys = p.hist_keys ? p.hist_rows.v[b] : p.Nq;
-  const int jc = (item.tile * 4 + kw) * 32 + i32;
-  const bool live = jc < n_keys;
+  const int jc = (item.tile * 4 + kw) * 32 + i16;
   const int ntiles = (p.Nq + QT - 1) / QT;
-  // first query row that sees this lane's key (ring rows are seen by every query), the
+  // first query row that sees each of this lane's keys (ring rows are seen by every query), the
   // largest over the wave (its last key) and the smallest over the workgroup (its first key)
   const int block_rows = p.hist_keys ? 0 : p.block_rows;
   const int j_last = n_keys - 1;
-  const int first_q = first_query_row_seeing(jc < j_last ? jc : j_last, block_rows);
+  int first_q[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) first_q[ks] = first_query_row_seeing(jc + 16 * ks < j_last ? jc + 16 * ks : j_last, block_rows);
   const int j_wave = (item.tile * 4 + kw) * 32 + 31;
   const int first_q_wave = first_query_row_seeing(j_wave < j_last ? j_wave : j_last, block_rows);
   const int t_begin = first_query_row_seeing(item.tile * 128, block_rows) / QT;
@@ -420,28 +451,30 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
     w.init(lane);
   else
     w.init(lane, p.scale_log2e);
-  {
-    // B operand of the role's first product: V row (key wave) or K~ row (value wave) of the lane's key
-    const int j0 = live ? jc : 0;
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    // B operand of the role's first product: V row (key wave) or K~ row (value wave) of the lane's key ks
+    const bool live = jc + 16 * ks < n_keys;
+    const int j0 = live ? jc + 16 * ks : 0;
     const __bf16* row;
     if constexpr (kKey)
       row = p.hist_keys ? p.v_cache + (bh * p.cache_rows + j0) * D : p.v_chunk + (((int64_t)b * p.Nq + j0) * p.H + h) * D;
     else
       row = p.hist_keys ? p.k_cache + (bh * p.cache_rows + j0) * D : p.kc_rot + (bh * p.Nq + j0) * D;
 #pragma unroll
-    for (int st = 0; st < D / 16; ++st) {
+    for (int st = 0; st < D / 32; ++st) {
       bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (live) x = *reinterpret_cast<const bf16x8*>(row + st * 16 + g * 8);
+      if (live) x = *reinterpret_cast<const bf16x8*>(row + st * 32 + g * 8);
       if constexpr (kKey)
-        w.vreg[st] = x;
+        w.vreg[ks][st] = x;
       else
-        w.kreg[st] = x;
+        w.kreg[ks][st] = x;
     }
   }
 
   const RowSegment q_rows = make_segment(p.q_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment do_rows = make_segment(p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, QT, kPairWaves> ts;
+  TileStreamer<D, QT, kPairWaves, true> ts;
   ts.init();
   const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
   // Row terms of a tile's queries: wave 0 fetches LSE*log2e and wave 1 Delta with a direct-to-LDS
@@ -476,10 +509,12 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
                reinterpret_cast<const float*>(lds + L::kTerms + PREV * L::SLOT_TERMS) + QT,
                lds + L::kProbs + PREV * L::SLOT_PROBS + probs_lane);
     } else {
-      if (n < ntiles)
+      if (n < ntiles) {
+        const int first[2] = {first_q[0] - n * QT, first_q[1] - n * QT};
         w.tile(lds + S * L::SLOT_TILES, lds + S * L::SLOT_TILES + L::TILE_BYTES,
                reinterpret_cast<const float*>(lds + L::kTerms + S * L::SLOT_TERMS),
-               lds + L::kProbs + S * L::SLOT_PROBS + probs_lane, first_q - n * QT, first_q_wave - n * QT);
+               lds + L::kProbs + S * L::SLOT_PROBS + probs_lane, first, first_q_wave - n * QT);
+      }
     }
     wait_vmem();
     __syncthreads();
@@ -493,27 +528,28 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
     if (++n > ntiles) break;
   }
 
-  if (live) {
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int j = jc + 16 * ks;
+    if (j >= n_keys) continue;
     float* row;
     if constexpr (kKey)
-      row = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + jc) * D : p.dk_rot + (bh * p.Nq + jc) * D;
+      row = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + j) * D : p.dk_rot + (bh * p.Nq + j) * D;
     else
-      row = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + jc) * p.H + h) * D
-                        : p.dv + (((int64_t)b * p.Nq + jc) * p.H + h) * D;
+      row = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + j) * p.H + h) * D
+                        : p.dv + (((int64_t)b * p.Nq + j) * p.H + h) * D;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int dt = 0; dt < D / 16; ++dt) {
+      f32x4 x;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        f32x4 x;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          if constexpr (kKey)
-            x[c] = w.dk[db][4 * rr + c] * p.scale;
-          else
-            x[c] = w.dv[db][4 * rr + c];
-        }
-        *reinterpret_cast<f32x4*>(row + 32 * db + 8 * rr + 4 * g) = x;
+      for (int c = 0; c < 4; ++c) {
+        if constexpr (kKey)
+          x[c] = w.dk[dt][ks][c] * p.scale;
+        else
+          x[c] = w.dv[dt][ks][c];
       }
+      *reinterpret_cast<f32x4*>(row + 16 * dt + 4 * g) = x;
+    }
   }
 }
 

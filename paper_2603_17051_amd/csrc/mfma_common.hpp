@@ -128,15 +128,23 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// Chunk swizzle for the two access patterns of that shape: 16 lanes reading one chunk column of
-// 16 consecutive rows (row operand), and the transposing read of 8 consecutive rows x 2 chunks
-// by 32 lanes.  Depends on row mod 16 only.
+// Chunk swizzle for the two access patterns of that shape.  Depends on row mod 16 only.
+//  * row operand (ds_read_b128): lane (i, g) reads chunk c + g of row i.  The LDS serves such a
+//    read in four passes of 16 lanes: {0-3, 12-15, 20-23, 24-27}, {4-7, 8-11, 16-19, 28-31} and
+//    the same + 32, so one pass holds rows {0-3, 12-15} at chunk c and rows {4-11} at chunk c ^ 1;
+//  * column operand (transposing ds_read_b64): 32 lanes per pass read rows r .. r+7 (r = 0 or 8)
+//    at two neighbouring chunks {2k, 2k+1}.
+// Both are conflict-free when the swizzled chunk is 2 * pair(row) + (row >= 8) with pair()
+// distinct over rows 0-7 and over rows 8-15, and pair(rows 12-15) = pair(rows 0-3): pair(row) =
+// row for row < 8, (row + 4) mod 8 above.  With 8 chunks per row two rows share the 64 banks,
+// the row's parity picks the half, and the same holds with pair() over the rows of one parity.
 template <int CPR>
 __device__ __forceinline__ int swizzle16(int row) {
+  const int hi = (row >> 3) & 1;
   if constexpr (CPR == 16)
-    return ((row & 7) << 1) | ((row >> 3) & 1);
+    return (((row + (hi << 2)) & 7) << 1) | hi;
   else
-    return (((row >> 1) & 3) << 1) | ((row >> 3) & 1);
+    return ((((row >> 1) & 3) ^ (hi << 1)) << 1) | hi;
 }
 template <int D>
 __device__ __forceinline__ int lds_chunk_offset16(int row, int chunk) {  // in bytes
@@ -150,21 +158,19 @@ template <int D>
 struct OperandAddr16 {
   static constexpr int KS = D / 32;  // k-steps of a contraction over D
   static constexpr int DT = D / 16;  // 16-column tiles
-  uint32_t row[KS];    // 8 contiguous columns 32*step + 8g .. of row (lane % 16): A operand, contraction over D
-  uint32_t tr[DT][2];  // transposing read: rows 4g + 16*half + 0..3 of column 16*dt + lane % 16
+  uint32_t row[KS];  // 8 contiguous columns 32*step + 8g .. of row (lane % 16): A operand, contraction over D
+  uint32_t tr[DT];   // transposing read: rows 4g + 0..3 of column 16*dt + lane % 16
 
   __device__ __forceinline__ void init(int lane) {
     const int i16 = lane & 15, g = lane >> 4;
 #pragma unroll
     for (int st = 0; st < KS; ++st) row[st] = lds_chunk_offset16<D>(i16, 4 * st + g);
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int r = 4 * g + 16 * half + (i16 >> 2);
-        const int c = 16 * dt + 4 * (i16 & 3);
-        tr[dt][half] = lds_chunk_offset16<D>(r, c >> 3) + (c & 7) * 2;
-      }
+    for (int dt = 0; dt < DT; ++dt) {
+      const int r = 4 * g + (i16 >> 2);
+      const int c = 16 * dt + 4 * (i16 & 3);
+      tr[dt] = lds_chunk_offset16<D>(r, c >> 3) + (c & 7) * 2;
+    }
   }
 };
 
@@ -177,8 +183,8 @@ __device__ __forceinline__ bf16x8 read_rows16(const char* tile, uint32_t addr, i
 // k-slots 8g .. 8g+3 <- rows row32 + 4g + 0..3, k-slots 8g+4 .. 8g+7 <- rows row32 + 16 + 4g + 0..3:
 // the order in which the two 16x16 accumulators over those rows hand over their registers.
 template <int D>
-__device__ __forceinline__ bf16x8 read_cols16(const char* tile, const uint32_t (&addr)[2], int row32) {
-  return concat4(lds_read_tr4(tile + addr[0] + row32 * D * 2), lds_read_tr4(tile + addr[1] + row32 * D * 2));
+__device__ __forceinline__ bf16x8 read_cols16(const char* tile, uint32_t addr, int row32) {
+  return concat4(lds_read_tr4(tile + addr + row32 * D * 2), lds_read_tr4(tile + addr + (row32 + 16) * D * 2));
 }
 
 // ---- global -> LDS streaming of [TILE rows][D] bf16 tiles -------------------------------
