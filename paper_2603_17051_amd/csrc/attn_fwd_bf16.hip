@@ -53,121 +53,176 @@ struct FwdParams {
   StreamInts hist_rows;
 };
 
-// x *= a in place: keeps the accumulator in its registers on the rare rescale path
-__device__ __forceinline__ float scale_in_place(float x, float a) {
-  asm volatile("v_mul_f32 %0, %1, %0" : "+v"(x) : "v"(a));
-  return x;
-}
-
+// 16x16x32 MFMAs: a wave's 32 queries are two sub-blocks of 16 (qs); lane (i = lane % 16,
+// g = lane / 16) holds, for queries 16*qs + i, the accumulator rows 4g .. 4g+3 of every 16-row
+// tile, so a query's row statistics are spread over the four lanes i, i+16, i+32, i+48; they
+// are only combined at the end of the kernel and on the rare path that moves the reference.
 template <int D>
 struct FwdWave {
-  static constexpr int QSTEPS = D / 16;  // MFMA k-steps of the QK product
-  static constexpr int DB = D / 32;      // 32-row blocks of O^T
+  static constexpr int KS = D / 32;   // k-steps of the QK product
+  static constexpr int KF = 2 * KS;   // K operand fragments of a 32-key tile: step x 16-key half
+  static constexpr int DT = D / 16;   // 16-row tiles of O^T
 
-  bf16x8 qreg[QSTEPS];
-  f32x16 o[DB];
-  float mc, l_run;  // softmax reference in log2 units (scale*log2(e) * dot), per-lane partial row sum
-  OperandAddr<D> addr;
+  bf16x8 qreg[2][KS];
+  f32x4 o[DT][2];
+  float mc[2], l_run[2];  // softmax reference in log2 units (scale*log2(e) * dot), per-lane partial row sum
+  OperandAddr16<D> addr;
   int g;
   float scale_log2e;
 
   __device__ __forceinline__ void init(int lane, float sl2e) {
-    g = lane >> 5;
+    g = lane >> 4;
     scale_log2e = sl2e;
     addr.init(lane);
-    mc = kNegBig;
-    l_run = 0.f;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int qs = 0; qs < 2; ++qs) {
+      mc[qs] = kNegBig;
+      l_run[qs] = 0.f;
+    }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) o[dt][qs] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   // p = exp2(s * scale*log2(e) - mc) rounded to bf16, packed as the B operands of the PV
-  // product; returns this lane's part of the row sum, taken over the rounded values.
-  __device__ __forceinline__ float probabilities(const f32x16 s, bf16x8 (&pb)[2]) const {
-    float sum = 0.f;
+  // product (k-slots 8g .. 8g+3 <- keys 4g .., 8g+4 .. <- keys 16 + 4g ..); sum = this lane's
+  // part of the row sums, taken over the rounded values.
+  __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][2], bf16x8 (&pb)[2], float (&sum)[2]) const {
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const f32x2 e = {fast_exp2(fmaf(s[r], scale_log2e, -mc)), fast_exp2(fmaf(s[r + 1], scale_log2e, -mc))};
-      const bf16x2 pk = __builtin_convertvector(e, bf16x2);
-      sum = add_pair(pk, sum);
-      pb[r >> 3][r & 7] = pk[0];
-      pb[r >> 3][(r & 7) + 1] = pk[1];
+    for (int qs = 0; qs < 2; ++qs) {
+      sum[qs] = 0.f;
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int r = 0; r < 4; r += 2) {
+          const f32x2 e = {fast_exp2(fmaf(s[kh][qs][r], scale_log2e, -mc[qs])),
+                           fast_exp2(fmaf(s[kh][qs][r + 1], scale_log2e, -mc[qs]))};
+          const bf16x2 pk = __builtin_convertvector(e, bf16x2);
+          sum[qs] = add_pair(pk, sum[qs]);
+          pb[qs][4 * kh + r] = pk[0];
+          pb[qs][4 * kh + r + 1] = pk[1];
+        }
     }
-    return sum;
   }
 
-  // A operands of the QK product: all 32 keys of the tile x D
-  __device__ __forceinline__ void read_k(const char* ks, bf16x8 (&kf)[QSTEPS]) const {
+  // A operands of the first half of the QK product's k-steps: 32 keys x D/2.  The other half is
+  // read behind the MFMAs of the first (registers for all of them at once are not there).
+  static constexpr int KH = KF / 2;
+  __device__ __forceinline__ void read_k(const char* ks, bf16x8 (&kf)[KH]) const {
 #pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) kf[st] = read_rows8<D>(ks, addr.row[st], 0);
+    for (int j = 0; j < KH; ++j) kf[j] = read_rows16<D>(ks, addr.row[j >> 1], 16 * (j & 1));
   }
 
   // S^T tile of 32 keys x this wave's 32 queries from K operands in registers.  With kTail
-  // and any_dead (wave-uniform), only the first `live` rows of the tile count for this lane's
-  // query: the others lie past their segment (K and V rows zero in LDS) or in a causal block
+  // and any_dead (wave-uniform), only the first live[qs] rows of the tile count for this lane's
+  // query qs: the others lie past their segment (K and V rows zero in LDS) or in a causal block
   // the query does not see, and get a score that makes their probability exactly 0.
   template <bool kTail>
-  __device__ __forceinline__ f32x16 scores(const bf16x8 (&kf)[QSTEPS], int live, bool any_dead) const {
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 s;
+  __device__ __forceinline__ void scores(const bf16x8 (&kf)[KH], const char* ks, const int (&live)[2], bool any_dead,
+                                         f32x4 (&s)[2][2]) const {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    bf16x8 hi[KH];
 #pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) s = mfma32(kf[st], qreg[st], st == 0 ? zero : s);
-    if (kTail && any_dead) {
+    for (int j = 0; j < KH; ++j) {  // fragment j: k-step j / 2, key half j % 2
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = acc_row(r, g) >= live ? kNegBig : s[r];
+      for (int qs = 0; qs < 2; ++qs) s[j & 1][qs] = mfma16(kf[j], qreg[qs][j >> 1], j < 2 ? zero : s[j & 1][qs]);
+      hi[j] = read_rows16<D>(ks, addr.row[(KH + j) >> 1], 16 * (j & 1));
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // then one LDS read
     }
-    return s;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < KH; ++j)
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) s[j & 1][qs] = mfma16(hi[j], qreg[qs][(KH + j) >> 1], s[j & 1][qs]);
+    if (kTail && any_dead) mask(live, s);
+  }
+
+  __device__ __forceinline__ void mask(const int (&live)[2], f32x4 (&s)[2][2]) const {
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s[kh][qs][r] = 16 * kh + 4 * g + r >= live[qs] ? kNegBig : s[kh][qs][r];
+  }
+
+  // The same scores for the rare path that moves the reference: every operand fragment is read
+  // right before its MFMAs, so the path adds no registers to what the common one needs.
+  template <bool kTail>
+  __device__ __forceinline__ void scores_again(const char* ks, const int (&live)[2], bool any_dead, f32x4 (&s)[2][2]) const {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < KF; ++j) {
+      const bf16x8 a = read_rows16<D>(ks, addr.row[j >> 1], 16 * (j & 1));
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) s[j & 1][qs] = mfma16(a, qreg[qs][j >> 1], j < 2 ? zero : s[j & 1][qs]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (kTail && any_dead) mask(live, s);
   }
 
   // One 32-key tile: kf = its K operands (read from ks), vs = its V rows in LDS; live (per
-  // lane) and any_dead (wave-uniform) are only looked at when kTail.
+  // lane and query) and any_dead (wave-uniform) are only looked at when kTail.
   template <bool kTail>
-  __device__ __forceinline__ void tile(const bf16x8 (&kf)[QSTEPS], const char* ks, const char* vs, int live,
+  __device__ __forceinline__ void tile(const bf16x8 (&kf)[KH], const char* ks, const char* vs, const int (&live)[2],
                                        bool any_dead) {
     // Probabilities relative to the current reference.  No maximum is taken on the common
     // path: a tile whose logits outgrow the reference shows up as a huge (or infinite) row
     // sum; only then the scores are computed again (the first copy is gone: the exponentials
     // are taken in place), the reference is raised and the probabilities are redone.
     bf16x8 pb[2];
-    float sum = probabilities(scores<kTail>(kf, live, any_dead), pb);
-    if (__builtin_expect(__any(!(sum <= kSumLimit)), 0)) {
-      bf16x8 kf2[QSTEPS];
-      read_k(ks, kf2);
-      const f32x16 s = scores<kTail>(kf2, live, any_dead);
-      float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-      mx = max_with_partner32(mx);
-      const float mc_new = fmaxf(mc, mx * scale_log2e);
-      const float alpha = fast_exp2(mc - mc_new);
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = scale_in_place(o[db][r], alpha);
-      mc = mc_new;
-      sum = probabilities(s, pb);
+    float sum[2];
+    {
+      f32x4 s[2][2];
+      scores<kTail>(kf, ks, live, any_dead, s);
+      probabilities(s, pb, sum);
     }
-    l_run += sum;
-    // O^T += V^T P^T (16 keys per MFMA k-step).  Only the operands of one k-step are in
-    // flight at a time: those of the second are read one by one behind the MFMAs of the
-    // first, into the registers these have just released.
-    bf16x8 v0[DB], v1[DB];
+    if (__builtin_expect(__any(!(sum[0] <= kSumLimit) || !(sum[1] <= kSumLimit)), 0)) {
+      f32x4 s[2][2];
+      scores_again<kTail>(ks, live, any_dead, s);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) v0[db] = read_cols8<D>(vs, addr.tr[db], 0);
+      for (int qs = 0; qs < 2; ++qs) {
+        float mx = fmaxf(fmaxf(s[0][qs][0], s[0][qs][1]), fmaxf(s[0][qs][2], s[0][qs][3]));
+        mx = fmaxf(mx, fmaxf(fmaxf(s[1][qs][0], s[1][qs][1]), fmaxf(s[1][qs][2], s[1][qs][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));  // over the four lanes that share the query
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mc_new = fmaxf(mc[qs], mx * scale_log2e);
+        const float alpha = fast_exp2(mc[qs] - mc_new);
+        l_run[qs] *= alpha;
+        // whole-tuple products: the compiler then updates the accumulators where they are
+        // (element by element it copies all of them, which the tile loop has no registers for)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt][qs] = o[dt][qs] * alpha;
+        mc[qs] = mc_new;
+      }
+      probabilities(s, pb, sum);
+    }
+    l_run[0] += sum[0];
+    l_run[1] += sum[1];
+    // O^T += V^T P^T.  Half of the V operand fragments are requested up front; those of the
+    // second half are read one by one behind the MFMAs of the first, into the registers
+    // these have just released.
+    constexpr int HALF = DT / 2;
+    bf16x8 v0[HALF], v1[HALF];
+#pragma unroll
+    for (int dt = 0; dt < HALF; ++dt) v0[dt] = read_cols16<D>(vs, addr.tr[dt], 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      o[db] = mfma32(v0[db], pb[0], o[db]);
-      v1[db] = read_cols8<D>(vs, addr.tr[db], 16);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+    for (int dt = 0; dt < HALF; ++dt) {
+      o[dt][0] = mfma16(v0[dt], pb[0], o[dt][0]);
+      o[dt][1] = mfma16(v0[dt], pb[1], o[dt][1]);
+      v1[dt] = read_cols16<D>(vs, addr.tr[HALF + dt], 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // two MFMAs
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // then two LDS reads
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) o[db] = mfma32(v1[db], pb[1], o[db]);
+    for (int dt = 0; dt < HALF; ++dt) {
+      o[HALF + dt][0] = mfma16(v1[dt], pb[0], o[HALF + dt][0]);
+      o[HALF + dt][1] = mfma16(v1[dt], pb[1], o[HALF + dt][1]);
+    }
   }
 };
 
@@ -181,7 +236,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile, V tile
   __shared__ __attribute__((aligned(1024))) char lds[kStages * STAGE_BYTES];
   // per-lane count of visible chunk rows: kept in LDS, not in a register the tile loop has no room for
-  __shared__ int vis_lds[kCausal ? kWaves * 64 : 1];
+  __shared__ int vis_lds[kCausal ? 2 * kWaves * 64 : 1];
 
   const WorkItem item = work_item(p.q_tiles, p.BH * p.splits, true);
   if (!item.valid) return;
@@ -189,10 +244,10 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const PairIndex pair = split_pair(item.bh / p.splits, p.H, p.group);
   const int b = pair.b, h = pair.h;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i32 = lane & 31, g = lane >> 5;
+  const int i16 = lane & 15, g = lane >> 4;
   const int hist = p.hist_rows.v[pair.cache_b];
-  const int q = (item.tile * kWaves + wave) * 32 + i32;
-  // chunk rows this lane's query sees, the fewest any lane of the wave sees (its first
+  const int q0 = (item.tile * kWaves + wave) * 32 + i16;  // this lane's queries: q0 and q0 + 16
+  // chunk rows each of this lane's queries sees, the fewest any lane of the wave sees (its first
   // query) and the most any wave of the workgroup sees (its last query)
   const int q_last = p.Nq - 1;
   const int block_rows = kCausal ? p.block_rows : 0;
@@ -200,7 +255,11 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const int q_wg = (item.tile + 1) * kWaves * 32 - 1;
   const int vis_wave = visible_chunk_rows(q_wave < q_last ? q_wave : q_last, p.Nq, block_rows);
   const int vis_wg = visible_chunk_rows(q_wg < q_last ? q_wg : q_last, p.Nq, block_rows);
-  if constexpr (kCausal) vis_lds[threadIdx.x] = visible_chunk_rows(q < q_last ? q : q_last, p.Nq, block_rows);
+  if constexpr (kCausal) {
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+      vis_lds[qs * kWaves * 64 + threadIdx.x] = visible_chunk_rows(q0 + 16 * qs < q_last ? q0 + 16 * qs : q_last, p.Nq, block_rows);
+  }
   // key tiles: first the resident ring rows, then the chunk rows the workgroup sees, each with its own tail
   const int hist_tiles = (hist + KT - 1) / KT;
   const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
@@ -211,14 +270,16 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
 
   Wave w;
   w.init(lane, p.scale_log2e);
-  // Q~ as the B operand: lane (i32, g) holds Q~[q][16*st + 8g .. +7]
-  {
+  // Q~ as the B operand: lane (i, g) holds Q~[q][32*st + 8g .. +7] of its two queries
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    const int q = q0 + 16 * qs;
     const __bf16* qrow = p.q_rot + (bh * p.Nq + (q < p.Nq ? q : 0)) * D;
 #pragma unroll
-    for (int st = 0; st < Wave::QSTEPS; ++st) {
+    for (int st = 0; st < Wave::KS; ++st) {
       bf16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (q < p.Nq) x = *reinterpret_cast<const bf16x8*>(qrow + st * 16 + g * 8);
-      w.qreg[st] = x;
+      if (q < p.Nq) x = *reinterpret_cast<const bf16x8*>(qrow + st * 32 + g * 8);
+      w.qreg[qs][st] = x;
     }
   }
 
@@ -226,7 +287,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  using Streamer = TileStreamer<D, KT, kWaves>;
+  using Streamer = TileStreamer<D, KT, kWaves, true>;
   Streamer ts;
   ts.init();
   const uint32_t off_dense = ts.lane_offset(k_hist);    // stride D: ring K, ring V, rotated chunk K
@@ -243,11 +304,11 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     ts.issue(ks, off_dense, row0, stage);
     ts.issue(vs, in_hist ? off_dense : off_vchunk, row0, stage + TILE_BYTES);
   };
-  // rows of tile t that count for this lane, and whether any lane of the wave has fewer than all
-  auto live_in = [&](int t) __attribute__((always_inline)) {
+  // rows of tile t that count for this lane's query qs, and whether any lane of the wave has fewer than all
+  auto live_in = [&](int t, int qs) __attribute__((always_inline)) {
     if (t < hist_tiles) return hist - t * KT;
     if constexpr (kCausal)
-      return vis_lds[threadIdx.x] - (t - hist_tiles) * KT;  // own entry: no barrier needed
+      return vis_lds[qs * kWaves * 64 + threadIdx.x] - (t - hist_tiles) * KT;  // own entry: no barrier needed
     else
       return vis_wave - (t - hist_tiles) * KT;
   };
@@ -275,7 +336,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     constexpr int MODE = decltype(mode_c)::value;
     char* stage = lds + ST * STAGE_BYTES;
     char* refill = lds + ((ST + kAhead) % kStages) * STAGE_BYTES;
-    bf16x8 kf[Wave::QSTEPS];
+    bf16x8 kf[Wave::KH];
     w.read_k(stage, kf);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == kHist)
@@ -283,10 +344,13 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     else if (t + kAhead < t_end)
       issue(t + kAhead, refill);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (MODE == kGeneric)
-      w.template tile<true>(kf, stage, stage + TILE_BYTES, live_in(t), any_dead_in(t));
-    else
-      w.template tile<false>(kf, stage, stage + TILE_BYTES, KT, false);
+    if constexpr (MODE == kGeneric) {
+      const int live[2] = {live_in(t, 0), live_in(t, 1)};
+      w.template tile<true>(kf, stage, stage + TILE_BYTES, live, any_dead_in(t));
+    } else {
+      const int live[2] = {KT, KT};
+      w.template tile<false>(kf, stage, stage + TILE_BYTES, live, false);
+    }
     // keep the next tile's K reads behind this tile's last MFMA: started earlier they
     // would need registers that are not there
     __builtin_amdgcn_sched_barrier(0);
@@ -312,26 +376,31 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   for (; t < t_end; t += kStages) group(t, std::integral_constant<int, kGeneric>{});
 
   // ---- epilogue: normalise, write O [B, Nq, H, D] bf16 and LSE [B, H, Nq] (of this split's keys)
-  const float l_tot = sum_with_partner32(w.l_run);
-  const float inv = 1.f / l_tot;
   __bf16* out = p.out;
   float* lse = p.lse;
   if (p.splits > 1) {
     out = p.out_part + (int64_t)split * ((int64_t)p.BH * p.Nq * D);
     lse = p.lse_part + (int64_t)split * ((int64_t)p.BH * p.Nq);
   }
-  if (q < p.Nq) {
-    __bf16* orow = out + (((int64_t)b * p.Nq + q) * p.H + h) * D;
 #pragma unroll
-    for (int db = 0; db < Wave::DB; ++db)
+  for (int qs = 0; qs < 2; ++qs) {
+    // the query's row sum: over the four lanes that share it
+    float l_tot = w.l_run[qs];
+    l_tot += __shfl_xor(l_tot, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    const float inv = 1.f / l_tot;
+    const int q = q0 + 16 * qs;
+    if (q < p.Nq) {
+      __bf16* orow = out + (((int64_t)b * p.Nq + q) * p.H + h) * D;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
+      for (int dt = 0; dt < Wave::DT; ++dt) {
         bf16x4 x;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) x[c] = (__bf16)(w.o[db][4 * rr + c] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * rr + 4 * g) = x;
+        for (int c = 0; c < 4; ++c) x[c] = (__bf16)(w.o[dt][qs][c] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 16 * dt + 4 * g) = x;
       }
-    if (g == 0) lse[bh * p.Nq + q] = w.mc * kLn2 + __logf(l_tot);
+      if (g == 0) lse[bh * p.Nq + q] = w.mc[qs] * kLn2 + __logf(l_tot);
+    }
   }
 }
 
