@@ -506,12 +506,9 @@ int bf16_fwd_splits(const DevGeom& g, const AttnOperands& op, bool have_parts) {
 
 hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, void* parts,
                                 hipStream_t stream) {
-  // The causal instantiation needs a few registers more than three workgroups per CU leave at
-  // D = 128 (it would reload a Q fragment from scratch in every tile: 4.0 ms instead of 3.5 ms
-  // at the 12-head, 1560-token, 21-frame shape), so it runs two workgroups per CU there.
   const bool causal = op.block_rows > 0;
   if (g.D == 128)
-    return causal ? launch<128, 3, 4, 2, true>(g, op, out, lse, parts, stream) : launch<128, 3, 4, 3, false>(g, op, out, lse, parts, stream);
+    return causal ? launch<128, 3, 4, 3, true>(g, op, out, lse, parts, stream) : launch<128, 3, 4, 3, false>(g, op, out, lse, parts, stream);
   return causal ? launch<64, 3, 4, 3, true>(g, op, out, lse, parts, stream) : launch<64, 3, 4, 3, false>(g, op, out, lse, parts, stream);
 }
 
