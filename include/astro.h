@@ -219,8 +219,8 @@ int astro_profile_end(astro_kernel_time_t *out, int32_t max_entries, int32_t *n_
 /* Machine calibration for the roofline the attention kernels are priced against (no
  * operation of the paper; both are timed through astro_profile_* under the names
  * "calib_mfma_bf16" and "calib_copy").
- * astro_calib_mfma: `workgroups` workgroups of 4 waves issue nothing but bf16 32x32x16
- *   MFMAs: iters * 16 per wave, 32768 flop each.  operands: device, 8 * 256 * 16 bytes of
+ * astro_calib_mfma: `workgroups` workgroups of 4 waves issue nothing but bf16 16x16x32
+ *   MFMAs (the shape the attention kernels use): iters * 32 per wave, 16384 flop each.  operands: device, 8 * 256 * 16 bytes of
  *   bf16 (4 A and 4 B fragments per lane); the clock the chip sustains depends on their
  *   values (all zero vs N(0,1)).  sink: device, workgroups * 256 floats, overwritten.
  *   workgroups in 1 .. 65536, iters in 1 .. 2^20.

@@ -210,7 +210,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
   const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, KT, kWaves, true> ts;
+  TileStreamer<D, KT, kWaves> ts;
   ts.init();
   const uint32_t off_dense = ts.lane_offset(k_hist);
   const uint32_t off_vchunk = ts.lane_offset(v_chunk);
@@ -474,7 +474,7 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
 
   const RowSegment q_rows = make_segment(p.q_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment do_rows = make_segment(p.dout + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  TileStreamer<D, QT, kPairWaves, true> ts;
+  TileStreamer<D, QT, kPairWaves> ts;
   ts.init();
   const uint32_t off_q = ts.lane_offset(q_rows), off_do = ts.lane_offset(do_rows);
   // Row terms of a tile's queries: wave 0 fetches LSE*log2e and wave 1 Delta with a direct-to-LDS

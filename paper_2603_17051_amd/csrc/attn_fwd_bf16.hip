@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const RowSegment v_hist = make_segment(p.v_cache + (int64_t)pair.cache_bh * p.cache_rows * D, D, hist, D);
   const RowSegment k_chunk = make_segment(p.kc_rot + bh * p.Nq * D, D, p.Nq, D);
   const RowSegment v_chunk = make_segment(p.v_chunk + ((int64_t)b * p.Nq * p.H + h) * D, (int64_t)p.H * D, p.Nq, D);
-  using Streamer = TileStreamer<D, KT, kWaves, true>;
+  using Streamer = TileStreamer<D, KT, kWaves>;
   Streamer ts;
   ts.init();
   const uint32_t off_dense = ts.lane_offset(k_hist);    // stride D: ring K, ring V, rotated chunk K

@@ -10,8 +10,9 @@ namespace {
 constexpr int kOperandSets = 4;
 
 // Each wave keeps 4 A and 4 B operand fragments in registers and issues independent
-// 32x32x16 MFMAs into 4 accumulators, pairing the fragments differently each time so that
-// the multiplier inputs change between consecutive instructions as they do in a real tile loop.
+// 16x16x32 MFMAs (the shape the attention kernels use) into 8 accumulators, pairing the
+// fragments differently each time so that the multiplier inputs change between consecutive
+// instructions as they do in a real tile loop.  32 MFMAs of 16384 flop per iteration.
 __global__ void __launch_bounds__(256, 2) calib_mfma_kernel(const bf16x8* __restrict__ operands, float* __restrict__ sink,
                                                             int iters) {
   bf16x8 a[kOperandSets], b[kOperandSets];
@@ -20,22 +21,20 @@ __global__ void __launch_bounds__(256, 2) calib_mfma_kernel(const bf16x8* __rest
     a[j] = operands[(2 * j) * 256 + threadIdx.x];
     b[j] = operands[(2 * j + 1) * 256 + threadIdx.x];
   }
-  f32x16 c[kOperandSets];
+  f32x4 c[2 * kOperandSets];
 #pragma unroll
-  for (int j = 0; j < kOperandSets; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) c[j][r] = 0.f;
+  for (int j = 0; j < 2 * kOperandSets; ++j) c[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int i = 0; i < iters; ++i) {
 #pragma unroll
     for (int u = 0; u < kOperandSets; ++u)
 #pragma unroll
-      for (int j = 0; j < kOperandSets; ++j) c[j] = mfma32(a[(j + u) % kOperandSets], b[j], c[j]);
+      for (int j = 0; j < 2 * kOperandSets; ++j) c[j] = mfma16(a[(j + u) % kOperandSets], b[j % kOperandSets], c[j]);
   }
   float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < kOperandSets; ++j)
+  for (int j = 0; j < 2 * kOperandSets; ++j)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += c[j][r];
+    for (int r = 0; r < 4; ++r) s += c[j][r];
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 

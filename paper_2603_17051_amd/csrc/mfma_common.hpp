@@ -12,7 +12,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -20,45 +19,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf (no inf - inf)
-
-// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].
-// Lane l (i = l % 32, g = l / 32) holds A[i][8g .. 8g+7], B[8g .. 8g+7][i] and
-// D[8*(r/4) + 4g + r%4][i] in accumulator register r.
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-// Row of a 32x32 accumulator tile that register r of lane group g holds.
-__device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
-
-// Value of the partner lane (l ^ 32) combined with the own one: v_permlane32_swap
-// exchanges the upper half of its first operand with the lower half of the second.
-__device__ __forceinline__ float max_with_partner32(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float sum_with_partner32(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// LDS tiles are [rows][D] bf16 in 16-byte chunks; chunk c of row r is stored at chunk
-// position c ^ swizzle(r) so that both access patterns of the kernels spread over the
-// banks: 32 lanes reading one chunk column of 32 consecutive rows (row operand of a
-// QK-type product), and the transposing read of 8 consecutive rows x 4 chunks.
-// swizzle(r) depends on r mod 16 only.
-template <int CPR>
-__device__ __forceinline__ int swizzle(int row) {
-  if constexpr (CPR == 16)
-    return ((row & 3) << 2) | ((row >> 2) & 3);
-  else
-    return row & (CPR - 1);
-}
-template <int D>
-__device__ __forceinline__ int lds_chunk_offset(int row, int chunk) {  // in bytes
-  constexpr int CPR = D / 8;
-  return (row * CPR + (chunk ^ swizzle<CPR>(row))) * 16;
-}
 
 // Transposing read (ds_read_b64_tr_b16): within each block of 16 lanes the lanes
 // 4r .. 4r+3 together supply row r (16 values) of a 4x16 matrix, and lane i receives
@@ -82,44 +42,7 @@ __device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
 }
 
-// Per-lane LDS byte offsets of the two operand access patterns of a [rows][D] tile, for
-// the first 32-row block / first 16 rows; further blocks are constant offsets because
-// the swizzle has period 16 rows.
-template <int D>
-struct OperandAddr {
-  static constexpr int QSTEPS = D / 16;
-  static constexpr int DB = D / 32;
-  uint32_t row[QSTEPS];  // 8 contiguous columns 16*st + 8g .. of row (lane % 32): A operand, contraction over D
-  uint32_t tr[DB][2];    // transposing read: rows 4g + 8*half + 0..3 of column 32*db + lane % 32
-
-  __device__ __forceinline__ void init(int lane) {
-    const int i32 = lane & 31, i16 = lane & 15, blk = (lane >> 4) & 1, g = lane >> 5;
-#pragma unroll
-    for (int st = 0; st < QSTEPS; ++st) row[st] = lds_chunk_offset<D>(i32, 2 * st + g);
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int r = 4 * g + 8 * half + (i16 >> 2);
-        const int c = 32 * db + 16 * blk + 4 * (i16 & 3);
-        tr[db][half] = lds_chunk_offset<D>(r, c >> 3) + (c & 7) * 2;
-      }
-  }
-};
-
-template <int D>
-__device__ __forceinline__ bf16x8 read_rows8(const char* tile, uint32_t addr, int block32) {
-  return *reinterpret_cast<const bf16x8*>(tile + addr + block32 * 32 * D * 2);
-}
-// A operand of a product contracting over 16 tile rows starting at row16 (a multiple of 16):
-// k-slots 8g .. 8g+3 <- rows row16 + 4g + 0..3, k-slots 8g+4 .. 8g+7 <- rows row16 + 8 + 4g + 0..3,
-// the same row order in which a 32x32 accumulator hands over its registers 8*(row16/16 % 2) ..
-template <int D>
-__device__ __forceinline__ bf16x8 read_cols8(const char* tile, const uint32_t (&addr)[2], int row16) {
-  return concat4(lds_read_tr4(tile + addr[0] + row16 * D * 2), lds_read_tr4(tile + addr[1] + row16 * D * 2));
-}
-
-// ---- the same for tiles read as operands of v_mfma_f32_16x16x32_bf16 ----------------------
+// ---- tiles read as operands of v_mfma_f32_16x16x32_bf16 ------------------------------------
 // D[16x16] += A[16x32] * B[32x16].  Lane l (i = l % 16, g = l / 16) holds A[i][8g .. 8g+7],
 // B[8g .. 8g+7][i] and D[4g + r][i] in accumulator register r.  Under the chip's power limit this
 // shape sustains about 16 % more flop/s than 32x32x16 on N(0,1) operands (1963 vs 1695 TFLOP/s
@@ -206,8 +129,7 @@ __device__ __forceinline__ RowSegment make_segment(const __bf16* base, int64_t s
   return s;
 }
 
-// kFor16: the tile is read with the 16x16x32 access patterns (swizzle16)
-template <int D, int TILE, int WAVES, bool kFor16 = false>
+template <int D, int TILE, int WAVES>
 struct TileStreamer {
   static constexpr int CPR = D / 8;                    // 16-byte chunks per row
   static constexpr int kRowsPerInst = 64 / CPR;        // rows one wave instruction covers
@@ -219,7 +141,7 @@ struct TileStreamer {
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     lane_row = wave * kRowsPerInst + lane / CPR;  // row within the first pass of the tile
-    lane_chunk_bytes = ((lane % CPR) ^ (kFor16 ? swizzle16<CPR>(lane_row) : swizzle<CPR>(lane_row))) * 16;
+    lane_chunk_bytes = ((lane % CPR) ^ swizzle16<CPR>(lane_row)) * 16;
   }
   // per-lane byte offset of its row/chunk inside a tile of a source with this stride
   __device__ __forceinline__ uint32_t lane_offset(const RowSegment s) const {
