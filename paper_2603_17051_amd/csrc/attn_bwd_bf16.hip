@@ -32,8 +32,8 @@ struct BwdParams {
   const __bf16* out;
   const __bf16* dout;
   const float* lse;
-  float* delta;   // [B][H][Nq]  <dO, O>
-  float* lse2;    // [B][H][Nq]  LSE * log2(e), written next to delta by the dQ kernel
+  float* delta;   // [B][H][Nq]  -<dO, O>
+  float* lse2;    // [B][H][Nq]  -LSE * log2(e), written next to delta by the dQ kernel
   float* dq_rot;  // [B][H][Nq][D]
   float* dk_rot;  // [B][H][Nq][D]
   float* dv;      // [B, Nq, H, D]
@@ -56,7 +56,10 @@ struct DqWave {
   static constexpr int KS = D / 32;  // k-steps of a contraction over D
   static constexpr int DT = D / 16;  // 16-row tiles of dQ~^T
   bf16x8 qreg[2][KS], doreg[2][KS];  // B operands: Q~ and dO rows of this lane's two queries
-  float lse2[2], delta[2];
+  float neg_lse2[2];   // -LSE*log2(e) of the two queries
+  // -Delta of the two queries, four copies each: the accumulators of dP^T start from them, so
+  // the product comes out as dP^T - Delta
+  f32x4 neg_delta[2];
   f32x4 dq[DT][2];
   OperandAddr16<D> addr;
   int g;
@@ -106,14 +109,14 @@ struct DqWave {
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
       __builtin_amdgcn_sched_barrier(0);
-      // dP^T = V dO^T
+      // dP^T = V dO^T, minus Delta
 #pragma unroll
       for (int st = 0; st < KS; ++st)
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
           const bf16x8 a = read_rows16<D>(vs, addr.row[st], 32 * kb + 16 * kh);
 #pragma unroll
-          for (int qs = 0; qs < 2; ++qs) dp[kh][qs] = mfma16(a, doreg[qs][st], st == 0 ? zero : dp[kh][qs]);
+          for (int qs = 0; qs < 2; ++qs) dp[kh][qs] = mfma16(a, doreg[qs][st], st == 0 ? neg_delta[qs] : dp[kh][qs]);
         }
       __builtin_amdgcn_sched_barrier(0);
       // dS^T = P^T o (dP^T - Delta), P^T = exp2(S^T * scale*log2(e) - LSE*log2(e)); as the B operand
@@ -124,10 +127,8 @@ struct DqWave {
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float pr = fast_exp2(fmaf(s[kh][qs][r], scale_log2e, -lse2[qs]));
-            dsb[qs][4 * kh + r] = (__bf16)(pr * (dp[kh][qs][r] - delta[qs]));
-          }
+          for (int r = 0; r < 4; ++r)
+            dsb[qs][4 * kh + r] = (__bf16)(fast_exp2(fmaf(s[kh][qs][r], scale_log2e, neg_lse2[qs])) * dp[kh][qs][r]);
       __builtin_amdgcn_sched_barrier(0);
       // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
 #pragma unroll
@@ -197,12 +198,13 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
     dsum += __shfl_xor(dsum, 16);
     dsum += __shfl_xor(dsum, 32);
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
-    w.lse2[qs] = live ? p.lse[bh * p.Nq + q] * kLog2e : 1.0e30f;
-    w.delta[qs] = dsum;
-    // the row terms of the query, for the dK/dV kernel
+    const float nl = live ? -p.lse[bh * p.Nq + q] * kLog2e : -1.0e30f;
+    w.neg_lse2[qs] = nl;
+    w.neg_delta[qs] = f32x4{-dsum, -dsum, -dsum, -dsum};
+    // the row terms of the query, for the dK/dV kernel (negative there too)
     if (live && g == 0) {
-      p.delta[bh * p.Nq + q] = dsum;
-      p.lse2[bh * p.Nq + q] = w.lse2[qs];
+      p.delta[bh * p.Nq + q] = -dsum;
+      p.lse2[bh * p.Nq + q] = nl;
     }
   }
 
@@ -311,7 +313,7 @@ struct ValueWave {
       for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // qs / dos = Q~ and dO tiles, lse_t = LSE*log2e of the tile's rows, probs = this wave's part of a P slot
+  // qs / dos = Q~ and dO tiles, lse_t = -LSE*log2(e) of the tile's rows, probs = this wave's part of a P slot
   __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs,
                                        const int (&first)[2], int first_max) {
 #pragma unroll
@@ -346,7 +348,7 @@ struct ValueWave {
 #pragma unroll
         for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) pb[ks][4 * qh + r] = (__bf16)fast_exp2(fmaf(s[qh][ks][r], scale_log2e, -l4[qh][r]));
+          for (int r = 0; r < 4; ++r) pb[ks][4 * qh + r] = (__bf16)fast_exp2(fmaf(s[qh][ks][r], scale_log2e, l4[qh][r]));
       *reinterpret_cast<bf16x8*>(probs + (2 * qb) * 1024) = pb[0];
       *reinterpret_cast<bf16x8*>(probs + (2 * qb + 1) * 1024) = pb[1];
       __builtin_amdgcn_sched_barrier(0);
@@ -379,25 +381,24 @@ struct KeyWave {
       for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // qs / dos = Q~ and dO tiles, delta_t = Delta of the tile's rows, probs = the partner's P of this tile
+  // qs / dos = Q~ and dO tiles, delta_t = -Delta of the tile's rows, probs = the partner's P of this tile
   __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* delta_t, const char* probs) {
 #pragma unroll
     for (int qb = 0; qb < QT / 32; ++qb) {
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
       f32x4 dp[2][2], d4[2];
       bf16x8 pb[2];
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh) d4[qh] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 16 * qh + 4 * g);
       pb[0] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb) * 1024);
       pb[1] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb + 1) * 1024);
-      // dP[q][key] = <dO_q, V_key>
+      // dP[q][key] - Delta[q] = <dO_q, V_key> - Delta[q]: the accumulators start from the rows' terms
 #pragma unroll
       for (int st = 0; st < KS; ++st)
 #pragma unroll
         for (int qh = 0; qh < 2; ++qh) {
           const bf16x8 a = read_rows16<D>(dos, addr.row[st], 32 * qb + 16 * qh);
 #pragma unroll
-          for (int ks = 0; ks < 2; ++ks) dp[qh][ks] = mfma16(a, vreg[ks][st], st == 0 ? zero : dp[qh][ks]);
+          for (int ks = 0; ks < 2; ++ks) dp[qh][ks] = mfma16(a, vreg[ks][st], st == 0 ? d4[qh] : dp[qh][ks]);
         }
       __builtin_amdgcn_sched_barrier(0);
       bf16x8 dsb[2];
@@ -407,7 +408,7 @@ struct KeyWave {
         for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            dsb[ks][4 * qh + r] = (__bf16)((float)pb[ks][4 * qh + r] * (dp[qh][ks][r] - d4[qh][r]));
+            dsb[ks][4 * qh + r] = (__bf16)((float)pb[ks][4 * qh + r] * dp[qh][ks][r]);
       __builtin_amdgcn_sched_barrier(0);
       // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
 #pragma unroll
