@@ -31,6 +31,18 @@ pairs with per-axis frequencies base**(-j/n_axis), temporal position = the
 absolute frame index, keys cached after rotation, values never rotated;
 gradients are returned for the un-rotated Q, K_chunk, V_chunk.
 
+Window-relative temporal positions (`window_relative=True`).  Sec. 4.3 only
+says that a positional-extrapolation method from another paper lets models
+trained on short clips run for long videos, and defines nothing.  The reading
+built here: the temporal position of a frame is its RANK in the sequence the
+chunk attends to -- sinks first (0 .. S-1), then the resident window frames
+from oldest to newest, then the chunk's own frames -- instead of its absolute
+index.  Ranks never exceed C + n_frames - 1 however long the stream runs, and
+the stream's start frame no longer matters.  Row and column positions are
+unchanged.  Relative to absolute positions this only moves the sinks: window
+and chunk frames are consecutive either way, while the distance from the
+sinks to the window stays S instead of growing with every eviction.
+
 Parity pins: tests/test_oracle_*.py (brute force, invariants, closed forms,
 library SDPA, finite differences).  The rotary pair layout and the
 attend-then-append order are fixed by this build, not by the paper: for those
@@ -138,10 +150,14 @@ class RingTableSim:
     def slot_frame(self) -> List[int]:
         return [-1 if m is None else self.start + m for m in self.slot_number]
 
-    def slot_pos(self) -> List[int]:
-        # temporal rotary position of the frame held by each slot (= its
-        # absolute frame index under reading 9); -1 for an empty slot
-        return self.slot_frame()
+    def slot_pos(self, window_relative: bool = False) -> List[int]:
+        # temporal rotary position of the frame held by each slot; -1 for an empty slot.
+        # Absolute: the frame's absolute index (reading 9).  Window-relative: its rank among
+        # the resident frames in stream order.
+        if not window_relative:
+            return self.slot_frame()
+        resident = sorted(m for m in self.slot_number if m is not None)
+        return [-1 if m is None else resident.index(m) for m in self.slot_number]
 
 
 # ----------------------------------------------------------------------------
@@ -175,7 +191,8 @@ class RollingCacheOracle:
     def __init__(self, batch: int, heads: int, head_dim: int, grid_h: int, grid_w: int,
                  capacity_frames: int, sink_frames: int, rope_pairs: Sequence[int],
                  rope_base: float = 10000.0, start_frames: Optional[Iterable[int]] = None,
-                 cache_rounding: bool = False, block_frames: Optional[int] = None):
+                 cache_rounding: bool = False, block_frames: Optional[int] = None,
+                 window_relative: bool = False):
         assert 0 <= sink_frames < capacity_frames
         assert block_frames is None or block_frames >= 1
         assert sum(rope_pairs) in (0, head_dim // 2)
@@ -191,6 +208,8 @@ class RollingCacheOracle:
         # k frames (the last may be shorter); a query sees the chunk keys of its own block
         # and of earlier blocks only.  The history is visible to every query either way.
         self.block_frames = block_frames
+        # temporal positions by rank in the attended sequence instead of absolute frame index
+        self.window_relative = window_relative
         starts = [0] * batch if start_frames is None else [int(s) for s in start_frames]
         self.start = starts
         # per stream: list of (K_frame [T,H,D], V_frame [T,H,D]) by reference
@@ -218,7 +237,7 @@ class RollingCacheOracle:
 
     def table_arrays(self):
         slot_frame = np.array([t.slot_frame() for t in self.tables], dtype=np.int32)
-        slot_pos = np.array([t.slot_pos() for t in self.tables], dtype=np.int32)
+        slot_pos = np.array([t.slot_pos(self.window_relative) for t in self.tables], dtype=np.int32)
         next_n = np.array([t.next_n for t in self.tables], dtype=np.int32)
         return slot_frame, slot_pos, next_n
 
@@ -230,9 +249,10 @@ class RollingCacheOracle:
         """Rotated keys and values of stream b's visible history for head h."""
         n0 = len(self.history[b])
         ks, vs = [], []
-        for n in visible_history(n0, self.S, self.Lw):
+        for rank, n in enumerate(visible_history(n0, self.S, self.Lw)):
             kf, vf = self.history[b][n]
-            kt = rope_rotate(np.asarray(kf[:, h:h + 1, :], dtype=np.float64), self._phi(self.start[b] + n))[:, 0]
+            pos = rank if self.window_relative else self.start[b] + n
+            kt = rope_rotate(np.asarray(kf[:, h:h + 1, :], dtype=np.float64), self._phi(pos))[:, 0]
             if self.cache_rounding:
                 kt = round_to_bf16(kt)
             ks.append(kt)
@@ -242,7 +262,10 @@ class RollingCacheOracle:
         return np.zeros((0, self.D)), np.zeros((0, self.D))
 
     def _chunk_phi(self, b: int, n_frames: int) -> np.ndarray:
-        f0 = self.start[b] + len(self.history[b])
+        if self.window_relative:  # the chunk continues the ranks of the visible history
+            f0 = len(visible_history(len(self.history[b]), self.S, self.Lw))
+        else:
+            f0 = self.start[b] + len(self.history[b])
         return np.concatenate([self._phi(f0 + i) for i in range(n_frames)], 0)
 
     def _visible(self, n_hist_rows: int, n_frames: int):
