@@ -306,6 +306,30 @@ def main() -> int:
             "dkv_kernel_ms": round(kt["attn_bwd_dkv_bf16"], 4)}
         ce.close()
         del qe, ke, ve, de, oe, le, g3, wse
+        # window-relative temporal positions at the long-streaming shape (ring of 12 = 1 sink + 11, batch 1):
+        # every evicting append also rotates the sink's keys again (2 x 4.8 MB); forward on the same cache
+        we = wl.WORKLOADS["stream_evict"]
+        ce = A.astro_kvcache_create(we.batch, we.heads, we.head_dim, we.grid_h, we.grid_w, we.capacity_frames,
+                                    we.sink_frames, we.chunk_frames, we.rope_pairs, we.rope_base, window_relative=True)
+        srcs = [tuple(dev_bf16(x) for x in wl.chunk_inputs(we, step=s)) for s in range(3)]
+        for i in range(6):   # fills the ring and starts evicting
+            A.astro_kvcache_append(ce, srcs[i % 3][1], srcs[i % 3][2], we.chunk_frames)
+        oe = torch.empty_like(srcs[0][0])
+        le = torch.empty((we.batch, we.heads, we.n_q), dtype=torch.float32, device=dev)
+        wse = torch.empty(A.astro_chunk_attn_workspace_bytes(ce, we.chunk_frames)[0], dtype=torch.uint8, device=dev)
+        A.astro_profile_begin()
+        for i in range(12):
+            qe, ke, ve = srcs[i % 3]
+            A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+            A.astro_kvcache_append(ce, ke, ve, we.chunk_frames)
+        kt = {k_: t / n_ for k_, (n_, t) in A.astro_profile_end().items()}
+        sink_bytes = 2 * we.batch * we.sink_frames * we.tokens_per_frame * we.heads * we.head_dim * 2
+        extras["window_relative_stream"] = {
+            "fwd_kernel_ms": round(kt["attn_fwd_bf16"], 4), "append_ms": round(kt["kv_append_rope"], 4),
+            "sink_rerotate_ms": round(kt["sink_rerotate"], 4),
+            "sink_rerotate_gbs": round(sink_bytes / (kt["sink_rerotate"] * 1e-3) / 1e9, 1)}
+        ce.close()
+        del srcs, oe, le, wse
         # fused clip-level loss: 24 (one group) and 192 candidate clips of 3 latent frames 16 x 60 x 104, bf16
         for n_clips in (24, 192):
             shape = (n_clips, 3 * 16 * 60 * 104)

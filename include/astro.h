@@ -29,6 +29,19 @@
  *   pair j of an axis with n pairs has frequency rope_base^(-j/n).  Keys are
  *   cached after rotation; values are never rotated.  All three counts 0 = no
  *   rotary embedding.
+ *
+ * Window-relative temporal positions (ASTRO_FLAG_WINDOW_RELATIVE).  Sec. 4.3 runs models
+ *   trained on short clips for long videos through a positional-extrapolation method it
+ *   only cites; the library's reading: the temporal position of a frame is its RANK in the
+ *   sequence a chunk attends to -- sinks 0 .. S-1, then the resident window frames from
+ *   oldest to newest, then the chunk's frames -- so no position exceeds C + n_frames - 1
+ *   however long the stream runs, and start_frame no longer matters.  Rows and columns
+ *   are unchanged.  Since rotary scores depend on position differences only, and window
+ *   and chunk frames are consecutive in both numberings, this equals keeping absolute
+ *   indices for them and moving the SINKS forward by the number of frames evicted so
+ *   far.  That is how it is stored: every append that evicts rotates the sinks' keys
+ *   again, from an un-rotated copy kept in k_sink_storage (one rounding, however often
+ *   they move), to their new position; the attention calls are unchanged.
  */
 #ifndef ASTRO_H_
 #define ASTRO_H_
@@ -52,6 +65,7 @@ extern "C" {
 
 /* desc.flags */
 #define ASTRO_FLAG_HOST_ONLY 1 /* no device work at all: the handle only plans slots  */
+#define ASTRO_FLAG_WINDOW_RELATIVE 2 /* temporal rotary positions by rank in the window   */
 
 #define ASTRO_MAX_BATCH 64
 #define ASTRO_MAX_CAPACITY_FRAMES 256
@@ -66,18 +80,25 @@ typedef struct astro_kvcache_desc {
   int32_t max_chunk_frames;           /* largest n_frames of any call, 1 .. C - S         */
   int32_t rope_pairs_t, rope_pairs_h, rope_pairs_w; /* sum == D/2, or all three 0         */
   int32_t dtype;                      /* ASTRO_BF16 or ASTRO_F32                          */
-  int32_t flags;                      /* 0 or ASTRO_FLAG_HOST_ONLY                        */
+  int32_t flags;                      /* bit set of ASTRO_FLAG_*                          */
   int32_t block_frames;               /* block size of the causal mask inside a chunk, in */
                                       /* frames; 0 = the whole chunk is one block         */
   double rope_base;                   /* > 1, e.g. 10000                                  */
   void *k_storage, *v_storage;        /* device, sizes from astro_kvcache_bytes; layout   */
                                       /* [B][H][C*T][D] of dtype; may be NULL iff         */
                                       /* ASTRO_FLAG_HOST_ONLY                             */
+  void *k_sink_storage;               /* device, astro_kvcache_sink_bytes: un-rotated     */
+                                      /* keys of the sink frames, [B, S*T, H, D] of dtype;*/
+                                      /* needed iff ASTRO_FLAG_WINDOW_RELATIVE with S > 0 */
+                                      /* and rotary pairs on the frame axis (not HOST_ONLY)*/
 } astro_kvcache_desc_t;
 
 /* Bytes of device storage the cache of `desc` needs for keys and for values
  * (Sec. 3.2: constant in the video length).  Host only. */
 int astro_kvcache_bytes(const astro_kvcache_desc_t *desc, size_t *k_bytes, size_t *v_bytes);
+
+/* Bytes of k_sink_storage for `desc` (0 when it is not needed).  Host only. */
+int astro_kvcache_sink_bytes(const astro_kvcache_desc_t *desc, size_t *bytes);
 
 /* Create a cache handle: all B streams empty, start frame 0.  Validates `desc`,
  * builds the per-row / per-column rotary tables in fp64 and uploads them (small,
@@ -98,13 +119,17 @@ int astro_kvcache_reset(astro_kvcache_t *cache, int32_t stream, int32_t start_fr
  * stream (0-based since reset) goes to ring slot n if n < C, else
  * S + (n - S) mod Lw, overwriting -- evicting -- frame n - Lw; keys are rotated
  * at absolute frame index start_frame + n and stored, values copied.
+ * With ASTRO_FLAG_WINDOW_RELATIVE the un-rotated keys of arriving sink frames are also
+ * copied to k_sink_storage, and once frames are evicted the sinks' keys in the ring are
+ * rotated again at start_frame + s + (frames evicted so far) in the same call.
  * 1 <= n_frames <= min(max_chunk_frames, Lw).  Advances the tables. */
 int astro_kvcache_append(astro_kvcache_t *cache, const void *k, const void *v, int32_t n_frames,
                          void *hip_stream);
 
 /* Host copies of the integer tables: slot_frame[B*C] = absolute index of the
  * frame resident in each ring slot (-1 = empty), slot_pos[B*C] = its temporal
- * rotary position (-1 = empty), next_n[B] = frames appended since reset.  Any
+ * rotary position (-1 = empty): the absolute index, or with ASTRO_FLAG_WINDOW_RELATIVE
+ * its rank among the resident frames; next_n[B] = frames appended since reset.  Any
  * output pointer may be NULL.  Host only (tables are host-authoritative). */
 int astro_kvcache_tables(const astro_kvcache_t *cache, int32_t *slot_frame, int32_t *slot_pos,
                          int32_t *next_n);

@@ -23,11 +23,12 @@ ASTRO_ERR_WORKSPACE = -5
 ASTRO_BF16 = 0
 ASTRO_F32 = 1
 ASTRO_FLAG_HOST_ONLY = 1
+ASTRO_FLAG_WINDOW_RELATIVE = 2
 ASTRO_MAX_BATCH = 64
 ASTRO_MAX_CAPACITY_FRAMES = 256
 
 EXPORTED = (
-    "astro_kvcache_bytes", "astro_kvcache_create", "astro_kvcache_destroy", "astro_kvcache_reset",
+    "astro_kvcache_bytes", "astro_kvcache_sink_bytes", "astro_kvcache_create", "astro_kvcache_destroy", "astro_kvcache_reset",
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
     "astro_group_attn_workspace_bytes", "astro_group_attn_fwd", "astro_group_attn_bwd",
@@ -45,7 +46,7 @@ class astro_kvcache_desc_t(ctypes.Structure):
         ("rope_pairs_t", c_int32), ("rope_pairs_h", c_int32), ("rope_pairs_w", c_int32),
         ("dtype", c_int32), ("flags", c_int32), ("block_frames", c_int32),
         ("rope_base", c_double),
-        ("k_storage", c_void_p), ("v_storage", c_void_p),
+        ("k_storage", c_void_p), ("v_storage", c_void_p), ("k_sink_storage", c_void_p),
     ]
 
 
@@ -67,6 +68,7 @@ def _load() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     P = POINTER
     lib.astro_kvcache_bytes.argtypes = [P(astro_kvcache_desc_t), P(c_size_t), P(c_size_t)]
+    lib.astro_kvcache_sink_bytes.argtypes = [P(astro_kvcache_desc_t), P(c_size_t)]
     lib.astro_kvcache_create.argtypes = [P(astro_kvcache_desc_t), P(c_void_p)]
     lib.astro_kvcache_destroy.argtypes = [c_void_p]
     lib.astro_kvcache_reset.argtypes = [c_void_p, c_int32, c_int32]
@@ -128,10 +130,10 @@ def _stream(stream) -> c_void_p:
 
 def make_desc(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
               rope_pairs=(0, 0, 0), rope_base=10000.0, dtype=ASTRO_BF16, flags=0,
-              k_storage=None, v_storage=None, block_frames=0) -> astro_kvcache_desc_t:
+              k_storage=None, v_storage=None, block_frames=0, k_sink_storage=None) -> astro_kvcache_desc_t:
     return astro_kvcache_desc_t(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames,
                                 max_chunk_frames, rope_pairs[0], rope_pairs[1], rope_pairs[2], dtype, flags, block_frames,
-                                float(rope_base), _ptr(k_storage), _ptr(v_storage))
+                                float(rope_base), _ptr(k_storage), _ptr(v_storage), _ptr(k_sink_storage))
 
 
 def astro_kvcache_bytes(desc: astro_kvcache_desc_t):
@@ -140,14 +142,21 @@ def astro_kvcache_bytes(desc: astro_kvcache_desc_t):
     return kb.value, vb.value
 
 
+def astro_kvcache_sink_bytes(desc: astro_kvcache_desc_t) -> int:
+    n = c_size_t(0)
+    _check(_lib.astro_kvcache_sink_bytes(byref(desc), byref(n)), "astro_kvcache_sink_bytes")
+    return n.value
+
+
 class KVCache:
     """Owner of one cache handle and of the torch tensors behind it."""
 
-    def __init__(self, handle: c_void_p, desc: astro_kvcache_desc_t, k_storage, v_storage):
+    def __init__(self, handle: c_void_p, desc: astro_kvcache_desc_t, k_storage, v_storage, k_sink_storage=None):
         self.handle = handle
         self.desc = desc
         self.k_storage = k_storage
         self.v_storage = v_storage
+        self.k_sink_storage = k_sink_storage
         self._workspace = None
 
     @property
@@ -176,20 +185,24 @@ class KVCache:
 
 def astro_kvcache_create(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
                          rope_pairs=(0, 0, 0), rope_base=10000.0, dtype=ASTRO_BF16, host_only=False,
-                         device="cuda:0", block_frames=0) -> KVCache:
+                         device="cuda:0", block_frames=0, window_relative=False) -> KVCache:
     """Allocate the K/V storage with torch (unless host_only) and create the handle."""
-    flags = ASTRO_FLAG_HOST_ONLY if host_only else 0
+    flags = (ASTRO_FLAG_HOST_ONLY if host_only else 0) | (ASTRO_FLAG_WINDOW_RELATIVE if window_relative else 0)
     desc = make_desc(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
                      rope_pairs, rope_base, dtype, flags, block_frames=block_frames)
-    k_storage = v_storage = None
+    k_storage = v_storage = k_sink_storage = None
     if not host_only:
         kb, vb = astro_kvcache_bytes(desc)
         k_storage = torch.zeros(kb, dtype=torch.uint8, device=device)
         v_storage = torch.zeros(vb, dtype=torch.uint8, device=device)
         desc.k_storage, desc.v_storage = _ptr(k_storage), _ptr(v_storage)
+        sb = astro_kvcache_sink_bytes(desc)
+        if sb:
+            k_sink_storage = torch.zeros(sb, dtype=torch.uint8, device=device)
+            desc.k_sink_storage = _ptr(k_sink_storage)
     handle = c_void_p(None)
     _check(_lib.astro_kvcache_create(byref(desc), byref(handle)), "astro_kvcache_create")
-    return KVCache(handle, desc, k_storage, v_storage)
+    return KVCache(handle, desc, k_storage, v_storage, k_sink_storage)
 
 
 def astro_kvcache_destroy(cache: KVCache) -> None:

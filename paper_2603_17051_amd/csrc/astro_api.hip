@@ -18,6 +18,7 @@ struct astro_kvcache {
   RingTables tables;
   void* k_storage;
   void* v_storage;
+  void* k_sink_storage = nullptr;  // un-rotated sink keys (window-relative positions only)
   // small library-owned device tables
   double* d_inv_freq_t = nullptr;
   float2* d_tab_h = nullptr;
@@ -151,6 +152,18 @@ int astro_kvcache_bytes(const astro_kvcache_desc_t* desc, size_t* k_bytes, size_
   return ASTRO_OK;
 }
 
+int astro_kvcache_sink_bytes(const astro_kvcache_desc_t* desc, size_t* bytes) {
+  astro_kvcache_desc_t d;
+  if (!desc || !bytes) return ASTRO_ERR_INVALID_ARG;
+  d = *desc;
+  d.flags |= ASTRO_FLAG_HOST_ONLY;
+  RingGeometry g;
+  const int rc = validate_desc(&d, &g);
+  if (rc != ASTRO_OK) return rc;
+  *bytes = g.sink_bytes();
+  return ASTRO_OK;
+}
+
 int astro_kvcache_create(const astro_kvcache_desc_t* desc, astro_kvcache_t** out) {
   if (!out) return ASTRO_ERR_INVALID_ARG;
   RingGeometry g;
@@ -158,6 +171,7 @@ int astro_kvcache_create(const astro_kvcache_desc_t* desc, astro_kvcache_t** out
   if (rc != ASTRO_OK) return rc;
   astro_kvcache* c = new (std::nothrow) astro_kvcache(g, desc->k_storage, desc->v_storage);
   if (!c) return ASTRO_ERR_INVALID_ARG;
+  c->k_sink_storage = desc->k_sink_storage;
   if (!g.host_only) {
     // rotary tables in fp64, rounded once to fp32
     std::vector<double> inv_t(g.n_t > 0 ? g.n_t : 1, 0.0);
@@ -218,9 +232,39 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
     StreamInts first, next;
     stream_ints(cache, &first, &next, nullptr);
     ScatterDst dst{cache->k_storage, cache->v_storage, (int64_t)g.C * g.T, 1};
-    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next,
-                            (hipStream_t)hip_stream) != hipSuccess)
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next, stream) != hipSuccess)
       return ASTRO_ERR_HIP;
+    if (g.sinks_move()) {
+      // Window-relative positions.  (1) Sink frames that arrive in this call: keep their keys
+      // un-rotated too.  (2) Streams whose eviction count changes: rotate their sinks again, at
+      // their own index plus the frames evicted once this call's frames are in.  An append holds at
+      // most Lw frames, so a call never does both for one stream.
+      const size_t frame_bytes = (size_t)g.T * g.H * g.D * g.elem_bytes();
+      StreamInts first_pos, count;
+      bool any = false;
+      for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
+        first_pos.v[b] = count.v[b] = 0;
+        if (b >= g.B) continue;
+        const int n0 = cache->tables.next_n(b), n1 = n0 + n_frames;
+        if (n0 < g.S) {
+          const int cnt = n1 < g.S ? n_frames : g.S - n0;
+          const char* src = (const char*)k + (size_t)b * n_frames * frame_bytes;
+          char* dstp = (char*)cache->k_sink_storage + ((size_t)b * g.S + n0) * frame_bytes;
+          if (hipMemcpyAsync(dstp, src, cnt * frame_bytes, hipMemcpyDeviceToDevice, stream) != hipSuccess)
+            return ASTRO_ERR_HIP;
+        }
+        const int ev0 = n0 > g.C ? n0 - g.C : 0, ev1 = n1 > g.C ? n1 - g.C : 0;
+        if (ev1 != ev0) {
+          first_pos.v[b] = cache->tables.start(b) + ev1;
+          count.v[b] = g.S;
+          any = true;
+        }
+      }
+      if (any && launch_rope_sink_rerotate(dev_geom(cache), g.dtype, cache->k_sink_storage, cache->k_storage, first_pos,
+                                           count, stream) != hipSuccess)
+        return ASTRO_ERR_HIP;
+    }
   }
   cache->tables.append(n_frames);
   return ASTRO_OK;
@@ -229,9 +273,11 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
 int astro_kvcache_tables(const astro_kvcache_t* cache, int32_t* slot_frame, int32_t* slot_pos, int32_t* next_n) {
   if (!cache) return ASTRO_ERR_INVALID_ARG;
   const std::vector<int32_t> sf = cache->tables.slot_frame();
-  // the temporal rotary position of a resident frame is its absolute frame index
+  // the temporal rotary position of a resident frame is its absolute frame index, or with
+  // window-relative positions its rank among the residents
+  const std::vector<int32_t> sp = cache->geo.window_relative ? cache->tables.slot_rank() : sf;
   if (slot_frame) std::memcpy(slot_frame, sf.data(), sf.size() * sizeof(int32_t));
-  if (slot_pos) std::memcpy(slot_pos, sf.data(), sf.size() * sizeof(int32_t));
+  if (slot_pos) std::memcpy(slot_pos, sp.data(), sp.size() * sizeof(int32_t));
   if (next_n)
     for (int b = 0; b < cache->geo.B; ++b) next_n[b] = cache->tables.next_n(b);
   return ASTRO_OK;
@@ -329,12 +375,14 @@ int astro_chunk_attn_bwd_full(astro_kvcache_t* cache, const void* q, const void*
   float* dk_hist_rot = (float*)(ws + w.dk_hist_rot);
   if (launch_attn_bwd_hist_bf16(d, op, lse, dout, dk_hist_rot, dv_cache, ws + w.scratch, stream) != hipSuccess)
     return ASTRO_ERR_HIP;
-  StreamInts start, next;
+  StreamInts start, next, sink_shift;
   for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
     start.v[b] = b < cache->geo.B ? cache->tables.start(b) : 0;
     next.v[b] = b < cache->geo.B ? cache->tables.next_n(b) : 0;
+    sink_shift.v[b] = b < cache->geo.B && cache->geo.sinks_move() ? cache->tables.evicted(b) : 0;
   }
-  if (launch_rope_unscatter_ring_f32(d, dk_hist_rot, dk_cache, start, next, stream) != hipSuccess) return ASTRO_ERR_HIP;
+  if (launch_rope_unscatter_ring_f32(d, dk_hist_rot, dk_cache, start, next, sink_shift, stream) != hipSuccess)
+    return ASTRO_ERR_HIP;
   return ASTRO_OK;
 }
 

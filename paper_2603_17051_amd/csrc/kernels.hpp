@@ -63,10 +63,19 @@ hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* 
 
 // The same for gradients of the ring rows: src [B][H][C*T][D] (rotated frame) -> dst
 // [B, C*T, H, D] w.r.t. the un-rotated keys; the frame a slot holds follows from start and
-// next_n (frames appended); rows of empty slots are not written.
+// next_n (frames appended); rows of empty slots are not written.  sink_shift.v[b] = how far
+// ahead of their own frame index stream b's sink slots are rotated (0 with absolute positions).
 hipError_t launch_rope_unscatter_ring_f32(const DevGeom& g, const float* src, float* dst,
                                           const StreamInts& start, const StreamInts& next_n,
-                                          hipStream_t stream);
+                                          const StreamInts& sink_shift, hipStream_t stream);
+
+// Window-relative temporal positions: rotate the sink frames' keys again from their un-rotated
+// copy sink_raw [B, S*T, H, D] into ring slots 0 .. S-1 of k_cache [B][H][C*T][D]; sink s of
+// stream b is rotated at frame position first_pos.v[b] + s, and only the first count.v[b]
+// sinks of stream b are touched (0 = leave the stream alone).
+hipError_t launch_rope_sink_rerotate(const DevGeom& g, int dtype, const void* sink_raw, void* k_cache,
+                                     const StreamInts& first_pos, const StreamInts& count,
+                                     hipStream_t stream);
 
 // Keys / values visible to a chunk: the resident ring rows (a prefix of the ring) and
 // the chunk's own rows.  With group > 1 the chunk tensors hold `group` candidate chunks per

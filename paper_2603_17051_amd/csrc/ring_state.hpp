@@ -16,10 +16,14 @@ struct RingGeometry {
   int n_t, n_h, n_w;
   int dtype;
   bool host_only;
+  bool window_relative;  // temporal positions by rank in the attended sequence
   double rope_base;
   size_t elem_bytes() const { return dtype == ASTRO_BF16 ? 2 : 4; }
   size_t rows_per_head() const { return (size_t)C * (size_t)T; }
   size_t storage_bytes() const { return (size_t)B * H * rows_per_head() * D * elem_bytes(); }
+  // the sinks' keys move only under window-relative positions, and only if the frame axis has rotary pairs
+  bool sinks_move() const { return window_relative && S > 0 && n_t > 0; }
+  size_t sink_bytes() const { return sinks_move() ? (size_t)B * S * T * H * D * elem_bytes() : 0; }
 };
 
 // Checks every field of the descriptor; fills `g` only on success.
@@ -39,10 +43,12 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   if (npairs != 0 && npairs != d->head_dim / 2) return ASTRO_ERR_INVALID_ARG;
   if (npairs != 0 && !(d->rope_base > 1.0)) return ASTRO_ERR_INVALID_ARG;
   if (d->dtype != ASTRO_BF16 && d->dtype != ASTRO_F32) return ASTRO_ERR_UNSUPPORTED;
-  if (d->flags & ~ASTRO_FLAG_HOST_ONLY) return ASTRO_ERR_INVALID_ARG;
+  if (d->flags & ~(ASTRO_FLAG_HOST_ONLY | ASTRO_FLAG_WINDOW_RELATIVE)) return ASTRO_ERR_INVALID_ARG;
   if (d->block_frames < 0) return ASTRO_ERR_INVALID_ARG;
   const bool host_only = (d->flags & ASTRO_FLAG_HOST_ONLY) != 0;
   if (!host_only && (!d->k_storage || !d->v_storage)) return ASTRO_ERR_INVALID_ARG;
+  const bool sinks_move = (d->flags & ASTRO_FLAG_WINDOW_RELATIVE) && d->sink_frames > 0 && d->rope_pairs_t > 0;
+  if (!host_only && sinks_move && !d->k_sink_storage) return ASTRO_ERR_INVALID_ARG;
   // token rows of one head's ring plus one chunk must index with int32
   const int64_t rows = (int64_t)(d->capacity_frames + d->max_chunk_frames) * d->grid_h * d->grid_w;
   if (rows > (int64_t)1 << 30) return ASTRO_ERR_UNSUPPORTED;
@@ -53,6 +59,7 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   g->block_frames = d->block_frames;
   g->n_t = d->rope_pairs_t; g->n_h = d->rope_pairs_h; g->n_w = d->rope_pairs_w;
   g->dtype = d->dtype; g->host_only = host_only; g->rope_base = d->rope_base;
+  g->window_relative = (d->flags & ASTRO_FLAG_WINDOW_RELATIVE) != 0;
   return ASTRO_OK;
 }
 
@@ -103,6 +110,18 @@ class RingTables {
   int32_t start(int b) const { return start_[b]; }
   int32_t next_n(int b) const { return next_n_[b]; }
   int32_t resident(int b) const { return next_n_[b] < C_ ? next_n_[b] : C_; }
+  // frames evicted so far = how far the sinks sit ahead of their own index under window-relative positions
+  int32_t evicted(int b) const { return next_n_[b] > C_ ? next_n_[b] - C_ : 0; }
+  // rank of every slot's frame among the residents in stream order, [B][C], -1 = empty
+  std::vector<int32_t> slot_rank() const {
+    std::vector<int32_t> t((size_t)B_ * C_, -1);
+    for (int b = 0; b < B_; ++b)
+      for (int s = 0; s < C_; ++s) {
+        const int64_t n = frame_number_in_slot(s, next_n_[b], C_, S_);
+        if (n >= 0) t[(size_t)b * C_ + s] = (int32_t)(n < S_ ? n : n - evicted(b));
+      }
+    return t;
+  }
   // absolute frame index held by every slot, [B][C], -1 = empty (closed form; the kernels that
   // need a slot's frame use the same function)
   std::vector<int32_t> slot_frame() const {

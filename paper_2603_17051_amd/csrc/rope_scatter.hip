@@ -173,15 +173,47 @@ __global__ void __launch_bounds__(kThreads) rope_unscatter_f32_kernel(DevGeom g,
 // slots are skipped (their rows of dst are not written)
 __global__ void __launch_bounds__(kThreads) rope_unscatter_ring_f32_kernel(DevGeom g, const float* __restrict__ src,
                                                                            float* __restrict__ dst, StreamInts start,
-                                                                           StreamInts next_n) {
+                                                                           StreamInts next_n, StreamInts sink_shift) {
   __shared__ float2 tab[kMaxBlockPairs];
   const int slot = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
   const int h = blockIdx.y, b = blockIdx.z;
   const int64_t n = frame_number_in_slot(slot, next_n.v[b], g.C, g.S);
   if (n < 0) return;  // whole block
   const bool rope = (g.n_t + g.n_h + g.n_w) != 0;
-  if (rope) fill_block_table(tab, g, start.v[b] + (int)n, row);
+  if (rope) fill_block_table(tab, g, start.v[b] + (int)n + (slot < g.S ? sink_shift.v[b] : 0), row);
   unrotate_row(g, tab, rope, src, dst, b, h, (int64_t)slot * g.T + (int64_t)row * g.gw, (int64_t)g.C * g.T);
+}
+
+// Sink keys rotated again at a new frame position (window-relative temporal positions): one
+// block = one token row of one sink frame of one head; un-rotated token-major rows in,
+// head-major ring rows (slot = the sink's own number) out.  A few MB per call: one 16-byte
+// chunk per lane at a time.
+template <typename Elem>
+__global__ void __launch_bounds__(kThreads) rope_sink_rerotate_kernel(DevGeom g, const Elem* __restrict__ sink_raw,
+                                                                      Elem* __restrict__ k_cache, StreamInts first_pos,
+                                                                      StreamInts count) {
+  constexpr int EPC = 16 / sizeof(Elem);
+  typedef Elem Chunk __attribute__((ext_vector_type(EPC)));
+  __shared__ float2 tab[kMaxBlockPairs];
+  const int s = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
+  const int h = blockIdx.y, b = blockIdx.z;
+  if (s >= count.v[b]) return;  // whole block
+  fill_block_table(tab, g, first_pos.v[b] + s, row);
+  const int cpr = g.D / EPC;
+  const int64_t in_tok0 = ((int64_t)b * g.S + s) * g.T + (int64_t)row * g.gw;
+  const int64_t out_row0 = ((int64_t)b * g.H + h) * ((int64_t)g.C * g.T) + (int64_t)s * g.T + (int64_t)row * g.gw;
+  for (int idx = threadIdx.x; idx < g.gw * cpr; idx += kThreads) {
+    const int w = idx / cpr, c = idx % cpr;
+    Chunk x = *reinterpret_cast<const Chunk*>(sink_raw + ((in_tok0 + w) * g.H + h) * g.D + c * EPC);
+#pragma unroll
+    for (int v = 0; v < EPC / 2; ++v) {
+      const float2 cs = pair_cs(tab, g, w, c * (EPC / 2) + v);
+      const float x0 = (float)x[2 * v], x1 = (float)x[2 * v + 1];
+      x[2 * v] = (Elem)(x0 * cs.x - x1 * cs.y);
+      x[2 * v + 1] = (Elem)(x0 * cs.y + x1 * cs.x);
+    }
+    *reinterpret_cast<Chunk*>(k_cache + (out_row0 + w) * g.D + c * EPC) = x;
+  }
 }
 
 }  // namespace
@@ -222,10 +254,21 @@ hipError_t launch_rope_unscatter_f32(const DevGeom& g, const float* src, float* 
 }
 
 hipError_t launch_rope_unscatter_ring_f32(const DevGeom& g, const float* src, float* dst, const StreamInts& start,
-                                          const StreamInts& next_n, hipStream_t stream) {
+                                          const StreamInts& next_n, const StreamInts& sink_shift, hipStream_t stream) {
   dim3 grid(g.C * g.gh, g.H, g.B), block(kThreads);
   ProfileScope prof("grad_rope_unstage_ring", stream);
-  rope_unscatter_ring_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, start, next_n);
+  rope_unscatter_ring_f32_kernel<<<grid, block, 0, stream>>>(g, src, dst, start, next_n, sink_shift);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_sink_rerotate(const DevGeom& g, int dtype, const void* sink_raw, void* k_cache,
+                                     const StreamInts& first_pos, const StreamInts& count, hipStream_t stream) {
+  dim3 grid(g.S * g.gh, g.H, g.B), block(kThreads);
+  ProfileScope prof("sink_rerotate", stream);
+  if (dtype == ASTRO_BF16)
+    rope_sink_rerotate_kernel<__bf16><<<grid, block, 0, stream>>>(g, (const __bf16*)sink_raw, (__bf16*)k_cache, first_pos, count);
+  else
+    rope_sink_rerotate_kernel<float><<<grid, block, 0, stream>>>(g, (const float*)sink_raw, (float*)k_cache, first_pos, count);
   return hipGetLastError();
 }
 

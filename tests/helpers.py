@@ -59,7 +59,7 @@ class Lockstep:
     """One GPU cache and one oracle fed the same frames."""
 
     def __init__(self, w: wl.Workload, dtype="bf16", start_frames=None, max_chunk=None, device="cuda:0",
-                 block_frames=0):
+                 block_frames=0, window_relative=False):
         import paper_2603_17051_amd as A
         self.A = A
         self.w = w
@@ -68,10 +68,11 @@ class Lockstep:
         self.cache = A.astro_kvcache_create(
             w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
             max_chunk or w.chunk_frames, w.rope_pairs, w.rope_base,
-            A.ASTRO_BF16 if dtype == "bf16" else A.ASTRO_F32, device=device, block_frames=block_frames)
+            A.ASTRO_BF16 if dtype == "bf16" else A.ASTRO_F32, device=device, block_frames=block_frames,
+            window_relative=window_relative)
         self.oracle = RollingCacheOracle(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames,
                                          w.sink_frames, w.rope_pairs, w.rope_base, start_frames,
-                                         block_frames=block_frames or None)
+                                         block_frames=block_frames or None, window_relative=window_relative)
         if start_frames is not None:
             for b, s in enumerate(start_frames):
                 A.astro_kvcache_reset(self.cache, b, int(s))

@@ -141,11 +141,33 @@ def test_group_workspace_scales_with_the_group_and_bad_groups_are_rejected():
     c.close()
 
 
+def test_window_relative_flag_sink_storage_and_unknown_flags():
+    lib = binding.library()
+    # sizes: un-rotated keys of the S sink frames, only when the sinks can move
+    d = A.make_desc(2, 12, 128, 30, 52, 12, 1, 3, (22, 21, 21), flags=binding.ASTRO_FLAG_WINDOW_RELATIVE)
+    assert A.binding.astro_kvcache_sink_bytes(d) == 2 * 1 * 1560 * 12 * 128 * 2
+    for desc in (A.make_desc(2, 12, 128, 30, 52, 12, 1, 3, (22, 21, 21)),                                    # flag off
+                 A.make_desc(2, 12, 128, 30, 52, 12, 0, 3, (22, 21, 21), flags=binding.ASTRO_FLAG_WINDOW_RELATIVE),  # no sinks
+                 A.make_desc(2, 12, 128, 30, 52, 12, 1, 3, (0, 32, 32), flags=binding.ASTRO_FLAG_WINDOW_RELATIVE),   # no frame pairs
+                 A.make_desc(2, 12, 128, 30, 52, 12, 1, 3, (0, 0, 0), flags=binding.ASTRO_FLAG_WINDOW_RELATIVE)):
+        assert A.binding.astro_kvcache_sink_bytes(desc) == 0
+    assert lib.astro_kvcache_sink_bytes(None, None) == binding.ASTRO_ERR_INVALID_ARG
+    # a device handle whose sinks move needs the sink storage (fake, never dereferenced pointers: creation
+    # is refused before anything touches the device)
+    d.k_storage = d.v_storage = ctypes.c_void_p(256)
+    h = ctypes.c_void_p(None)
+    assert lib.astro_kvcache_create(ctypes.byref(d), ctypes.byref(h)) == binding.ASTRO_ERR_INVALID_ARG
+    assert h.value is None
+    d.flags = 4
+    assert lib.astro_kvcache_sink_bytes(ctypes.byref(d), ctypes.byref(ctypes.c_size_t(0))) == binding.ASTRO_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("C,S,Fc,start", [(1, 0, 1, 0), (4, 0, 1, 0), (4, 1, 3, 7), (12, 1, 3, 0), (18, 0, 3, 41),
                                           (21, 3, 3, 0), (5, 4, 1, 2), (7, 2, 5, 1000), (256, 3, 11, 5)])
-def test_tables_follow_the_naive_ring_simulation(C, S, Fc, start):
+@pytest.mark.parametrize("window_relative", [False, True])
+def test_tables_follow_the_naive_ring_simulation(C, S, Fc, start, window_relative):
     B = 3
-    c = A.astro_kvcache_create(B, 1, 64, 2, 2, C, S, Fc, host_only=True)
+    c = A.astro_kvcache_create(B, 1, 64, 2, 2, C, S, Fc, host_only=True, window_relative=window_relative)
     starts = [start + 10 * b for b in range(B)]
     sims = [RingTableSim(C, S, s) for s in starts]
     for b, s in enumerate(starts):
@@ -160,7 +182,7 @@ def test_tables_follow_the_naive_ring_simulation(C, S, Fc, start):
                 sim.append_frame()
         sf, sp, nn = A.astro_kvcache_tables(c)
         assert sf == [sim.slot_frame() for sim in sims]
-        assert sp == [sim.slot_pos() for sim in sims]
+        assert sp == [sim.slot_pos(window_relative) for sim in sims]
         assert nn == [sim.next_n for sim in sims]
         n += k
         steps += 1
