@@ -75,6 +75,68 @@ struct DqWave {
       for (int qs = 0; qs < 2; ++qs) dq[dt][qs] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // ---- the pieces of one 32-key block kb of a tile -------------------------------------
+  // S^T = K Q~^T: 16 MFMAs, each pair behind the read of its K fragment
+  __device__ __forceinline__ void s_product(const char* ks, int kb, f32x4 (&s)[2][2]) const {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < KS; ++st)
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh) {
+        const bf16x8 a = read_rows16<D>(ks, addr.row[st], 32 * kb + 16 * kh);
+#pragma unroll
+        for (int qs = 0; qs < 2; ++qs) s[kh][qs] = mfma16(a, qreg[qs][st], st == 0 ? zero : s[kh][qs]);
+      }
+  }
+  // keys of the block that do not count for a query: score replaced so that P and dS are exactly 0
+  __device__ __forceinline__ void mask(int kb, const int (&live)[2], f32x4 (&s)[2][2]) const {
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s[kh][qs][r] = 32 * kb + 16 * kh + 4 * g + r >= live[qs] ? kNegBig : s[kh][qs][r];
+  }
+  // P^T = exp2(S^T * scale*log2(e) - LSE*log2(e)), in place: 32 vector-ALU instructions
+  __device__ __forceinline__ void probabilities(f32x4 (&s)[2][2]) const {
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s[kh][qs][r] = fast_exp2(fmaf(s[kh][qs][r], scale_log2e, neg_lse2[qs]));
+  }
+  // dP^T - Delta = V dO^T - Delta: 16 MFMAs
+  __device__ __forceinline__ void dp_product(const char* vs, int kb, f32x4 (&dp)[2][2]) const {
+#pragma unroll
+    for (int st = 0; st < KS; ++st)
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh) {
+        const bf16x8 a = read_rows16<D>(vs, addr.row[st], 32 * kb + 16 * kh);
+#pragma unroll
+        for (int qs = 0; qs < 2; ++qs) dp[kh][qs] = mfma16(a, doreg[qs][st], st == 0 ? neg_delta[qs] : dp[kh][qs]);
+      }
+  }
+  // dS^T = P^T o (dP^T - Delta) as the B operand of the next product (k-slots 8g .. 8g+3 <- keys
+  // 4g .., k-slots 8g+4 .. <- keys 16 + 4g ..): 24 vector-ALU instructions
+  __device__ __forceinline__ void ds_operand(const f32x4 (&pr)[2][2], const f32x4 (&dp)[2][2], bf16x8 (&dsb)[2]) const {
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dsb[qs][4 * kh + r] = (__bf16)(pr[kh][qs][r] * dp[kh][qs][r]);
+  }
+  // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]: 16 MFMAs
+  __device__ __forceinline__ void dq_product(const char* ks, int kb, const bf16x8 (&dsb)[2]) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 a = read_cols16<D>(ks, addr.tr[dt], 32 * kb);
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) dq[dt][qs] = mfma16(a, dsb[qs], dq[dt][qs]);
+    }
+  }
+
   // One 64-key tile of which the first live[qs] keys count for this lane's query qs (live_min,
   // wave-uniform: the fewest over the wave).  The others lie past the end of their segment
   // (zero rows in LDS) or in a causal block the query does not see; their score is replaced
@@ -84,59 +146,32 @@ struct DqWave {
   // product's fragments one MFMA behind the current one (no product then starts by waiting for
   // LDS) was measured slower with the 32x32x16 kernel, 5.05 vs 4.93 ms: it needs all 256
   // registers and the kernel is not bound by LDS latency.
+  // Vector-ALU instructions issue while an MFMA executes, also within one wave: the
+  // exponentials (which need S only) sit between the MFMAs of the dP product, 4.56 -> 4.41 ms.
+  // Going further lost: the dS operand of one query sub-block under the dQ MFMAs of the other
+  // (K^T fragments held for both: all 256 registers, 4.64 ms); the scores of the next key block
+  // carried along so that the dS operand sits under their MFMAs (spills in the tile loop, 7.4 ms).
   __device__ __forceinline__ void tile(const char* ks, const char* vs, const int (&live)[2], int live_min) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
       f32x4 s[2][2], dp[2][2];  // [16-key half][query sub-block]
-      // S^T = K Q~^T
-#pragma unroll
-      for (int st = 0; st < KS; ++st)
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-          const bf16x8 a = read_rows16<D>(ks, addr.row[st], 32 * kb + 16 * kh);
-#pragma unroll
-          for (int qs = 0; qs < 2; ++qs) s[kh][qs] = mfma16(a, qreg[qs][st], st == 0 ? zero : s[kh][qs]);
-        }
-      if (live_min < 32 * (kb + 1)) {
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-          for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) s[kh][qs][r] = 32 * kb + 16 * kh + 4 * g + r >= live[qs] ? kNegBig : s[kh][qs][r];
-      }
+      bf16x8 dsb[2];
+      s_product(ks, kb, s);
+      if (live_min < 32 * (kb + 1)) mask(kb, live, s);
       // keep the phases apart: hoisting every LDS read of a key block to its top costs
       // more registers than two resident waves per SIMD have
       __builtin_amdgcn_sched_barrier(0);
-      // dP^T = V dO^T, minus Delta
+      probabilities(s);
+      dp_product(vs, kb, dp);
 #pragma unroll
-      for (int st = 0; st < KS; ++st)
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-          const bf16x8 a = read_rows16<D>(vs, addr.row[st], 32 * kb + 16 * kh);
-#pragma unroll
-          for (int qs = 0; qs < 2; ++qs) dp[kh][qs] = mfma16(a, doreg[qs][st], st == 0 ? neg_delta[qs] : dp[kh][qs]);
-        }
-      __builtin_amdgcn_sched_barrier(0);
-      // dS^T = P^T o (dP^T - Delta), P^T = exp2(S^T * scale*log2(e) - LSE*log2(e)); as the B operand
-      // of the next product: k-slots 8g .. 8g+3 <- keys 4g .., k-slots 8g+4 .. <- keys 16 + 4g ..
-      bf16x8 dsb[2];
-#pragma unroll
-      for (int qs = 0; qs < 2; ++qs)
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            dsb[qs][4 * kh + r] = (__bf16)(fast_exp2(fmaf(s[kh][qs][r], scale_log2e, neg_lse2[qs])) * dp[kh][qs][r]);
-      __builtin_amdgcn_sched_barrier(0);
-      // dQ~^T[d][q] += K^T[d][key] dS^T[key][q]
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const bf16x8 a = read_cols16<D>(ks, addr.tr[dt], 32 * kb);
-#pragma unroll
-        for (int qs = 0; qs < 2; ++qs) dq[dt][qs] = mfma16(a, dsb[qs], dq[dt][qs]);
+      for (int i = 0; i < 4 * KS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // two vector-ALU instructions
       }
+      __builtin_amdgcn_sched_barrier(0);
+      ds_operand(s, dp, dsb);
+      __builtin_amdgcn_sched_barrier(0);
+      dq_product(ks, kb, dsb);
     }
   }
 };
