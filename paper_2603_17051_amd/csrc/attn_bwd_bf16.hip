@@ -150,7 +150,8 @@ struct DqWave {
   // exponentials (which need S only) sit between the MFMAs of the dP product, 4.56 -> 4.41 ms.
   // Going further lost: the dS operand of one query sub-block under the dQ MFMAs of the other
   // (K^T fragments held for both: all 256 registers, 4.64 ms); the scores of the next key block
-  // carried along so that the dS operand sits under their MFMAs (spills in the tile loop, 7.4 ms).
+  // carried along so that the dS operand sits under their MFMAs (spills in the tile loop, 7.4 ms);
+  // the first two operand fragments of the dP and dQ products requested one phase early (4.54 vs 4.48 ms).
   __device__ __forceinline__ void tile(const char* ks, const char* vs, const int (&live)[2], int live_min) {
 #pragma unroll
     for (int kb = 0; kb < KT / 32; ++kb) {
