@@ -23,8 +23,9 @@
 // accumulators and the bf16 exponent range make any smaller excess exact enough, and
 // both the row maximum and the 64 accumulator multiplies of a rescale leave the common path.
 // The softmax's vector-ALU work of a tile has no independent MFMAs of the same wave to sit between
-// (taking the probabilities of the first 16 keys between the MFMAs of the other 16 shortens the
-// accumulator chains to two and was measured slower, 3.34 vs 3.22 ms); the overlap comes from
+// (taking the probabilities of the first 16 keys between the MFMAs of the other 16 was measured
+// slower as the scheduler ordered it, 3.34 vs 3.22 ms, and equal with the exact order pinned in
+// assembly, 3.03-3.08 vs 3.01-3.03 ms); the overlap comes from
 // three workgroups (three waves per SIMD) being resident per CU.
 #include "kernels.hpp"
 #include "mfma_common.hpp"
