@@ -330,6 +330,43 @@ def main() -> int:
             "sink_rerotate_gbs": round(sink_bytes / (kt["sink_rerotate"] * 1e-3) / 1e9, 1)}
         ce.close()
         del srcs, oe, le, wse
+        # smallest shape (config 1: one 64-token frame over a ring of 4), forward + backward: eager calls against one HIP graph replay
+        we = wl.WORKLOADS["tiny_fwd"]
+        ce = make_cache(we)
+        qe, ke, ve, de = (dev_bf16(x) for x in wl.chunk_inputs(we, with_dout=True))
+        oe = torch.empty_like(qe)
+        le = torch.empty((we.batch, we.heads, we.n_q), dtype=torch.float32, device=dev)
+        g3 = [torch.empty(qe.shape, dtype=torch.float32, device=dev) for _ in range(3)]
+        wse = torch.empty(max(A.astro_chunk_attn_workspace_bytes(ce, we.chunk_frames)), dtype=torch.uint8, device=dev)
+
+        def tiny_step():
+            A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+            A.astro_chunk_attn_bwd(ce, qe, ke, ve, oe, le, de, we.chunk_frames, *g3, wse)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            tiny_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            tiny_step()
+        times = {}
+        for label, fn in (("eager", tiny_step), ("graph", graph.replay)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            n = 200
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            times[label] = (time.perf_counter() - t0) * 1e6 / n
+        extras["tiny_fwd_bwd_graph"] = {"eager_us": round(times["eager"], 1), "graph_replay_us": round(times["graph"], 1)}
+        del graph
+        ce.close()
+        del qe, ke, ve, de, oe, le, g3, wse
         # fused clip-level loss: 24 (one group) and 192 candidate clips of 3 latent frames 16 x 60 x 104, bf16
         for n_clips in (24, 192):
             shape = (n_clips, 3 * 16 * 60 * 104)
