@@ -170,3 +170,49 @@ def test_bf16_long_stream_shape_with_one_sink():
         print(f"    step {step}: {rep[-2]}", flush=True)
     check_sinks(ls)
     ls.close()
+
+
+def test_bf16_production_frames_two_streams_group_backward():
+    """1560-token frames, 12 heads; two streams at different points of their life (one still
+    filling its ring, one that has evicted many frames), two sinks; two candidates per stream,
+    forward and backward on sampled (candidate, head) pairs."""
+    import torch
+    w = wl.Workload("wr_prod", 35, 2, 12, 128, 30, 52, 8, 2, 3, 0, (22, 21, 21))
+    ls = Lockstep(w, start_frames=[0, 40], window_relative=True)
+    A, G, Fc = ls.A, 2, 3
+    pk, pv = wl.history_frame_pool(w, 6)
+    dk, dv = ls.dev(pk), ls.dev(pv)
+    fk, fv = wl.bf16_bits_to_f32(pk), wl.bf16_bits_to_f32(pv)
+    total = 19
+    for n in range(total):
+        if n == total - 5:   # stream 0 starts over: it will hold 5 frames (2 sinks + 3), nothing evicted
+            A.astro_kvcache_reset(ls.cache, 0, 7)
+            ls.oracle.reset(0, 7)
+        idx = [wl.pool_index(b, n, 6) for b in range(w.batch)]
+        it = torch.tensor(idx, device="cuda:0")
+        A.astro_kvcache_append(ls.cache, dk.index_select(0, it).contiguous(), dv.index_select(0, it).contiguous(), 1)
+        for b in range(w.batch):
+            ls.oracle.append_stream(b, fk[idx[b]], fv[idx[b]], 1)
+    ls.check_tables()
+    check_sinks(ls)
+    assert len(ls.oracle.history[0]) == 5 and len(ls.oracle.history[1]) == 19
+    q, k, v, do = (np.concatenate([a, b], 0) for a, b in zip(wl.chunk_inputs(w, 1, with_dout=True),
+                                                             wl.chunk_inputs(w, 2, with_dout=True)))
+    # candidates are ordered (stream, candidate): rows 0,1 belong to stream 0 and rows 2,3 to stream 1
+    order = [0, 2, 1, 3]
+    q, k, v, do = (x[order] for x in (q, k, v, do))
+    dq_, dk_, dv_, ddo = (ls.dev(x) for x in (q, k, v, do))
+    out, lse = A.astro_group_attn_fwd(ls.cache, dq_, dk_, dv_, Fc, G)
+    gq, gk, gv = A.astro_group_attn_bwd(ls.cache, dq_, dk_, dv_, out, lse, ddo, Fc, G)
+    qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in (q, k, v, do))
+    rep = []
+    for c, h in [(1, 3), (2, 10)]:
+        ro, rl = ls.oracle.group_attn_fwd(qf, kf, vf, Fc, G, candidates=[c], heads=[h])
+        rq, rk, rv = ls.oracle.group_attn_bwd(qf, kf, vf, dof, Fc, G, candidates=[c], heads=[h])
+        assert_bf16_close(host_f64(out[c, :, h]), ro[c, :, h], f"candidate {c} head {h} out", rep)
+        assert_bf16_close(host_f64(lse[c, h]), rl[c, h], f"candidate {c} head {h} lse", rep)
+        assert_bf16_close(host_f64(gq[c, :, h]), rq[c, :, h], f"candidate {c} head {h} dq", rep)
+        assert_bf16_close(host_f64(gk[c, :, h]), rk[c, :, h], f"candidate {c} head {h} dk", rep)
+        assert_bf16_close(host_f64(gv[c, :, h]), rv[c, :, h], f"candidate {c} head {h} dv", rep)
+    _report(rep)
+    ls.close()
