@@ -65,7 +65,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (streams and heads shard "
-              "without any exchange, see DESIGN.md)", file=sys.stderr)
+              "without any exchange between GPUs)", file=sys.stderr)
         return 2
 
     import numpy as np
