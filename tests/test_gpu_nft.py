@@ -33,6 +33,8 @@ def _case(n, shape, dtype, seed, masked):
     ("bf16", 5, (40,), (0, 3), 0.7, 2.0),
     ("bf16", 4, (3, 16, 20, 26), (), 1.0, 1.0),              # nothing masked; 24960 elements: two blocks per sample, ragged
     ("bf16", 24, (3, 16, 60, 104), (2, 5, 11, 23), 1.0, 0.1),   # 24 candidate clips of 3 latent frames (16 x 60 x 104)
+    ("bf16", 1024, (24,), (0, 17, 1023), 1.0, 0.3),            # the most samples the main launch prepares for itself
+    ("bf16", 1500, (16,), (3, 700, 1499), 0.9, 0.3),           # above it: separate prepare launch
 ])
 def test_nft_loss_and_gradient(dtype, n, shape, masked, beta, lam):
     import torch
