@@ -84,10 +84,10 @@ def main() -> int:
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
 
-    def make_cache(w, block_frames=0):
+    def make_cache(w, block_frames=0, reuse_staged=False):
         cache = A.astro_kvcache_create(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames,
                                        w.sink_frames, w.chunk_frames, w.rope_pairs, w.rope_base,
-                                       block_frames=block_frames)
+                                       block_frames=block_frames, reuse_staged=reuse_staged)
         pk, pv = wl.history_frame_pool(w, 4)
         dk, dv = dev_bf16(pk), dev_bf16(pv)
         for n in range(min(w.resident_frames, w.capacity_frames)):
@@ -96,8 +96,14 @@ def main() -> int:
         return cache
 
     # ---- main workload: fwd + bwd + append ---------------------------------------
-    cache = make_cache(w)
-    q, k, v, do = (dev_bf16(x) for x in wl.chunk_inputs(w, with_dout=True))
+    # The handle may reuse what a forward staged when the backward that follows it gets the same
+    # chunk and workspace (the re-forward + backward of gradient checkpointing).  Each step works
+    # on one of three distinct input sets (3 x 460 MB), so neither the attention kernels nor the
+    # append find their sources in the 256 MB last-level cache from the step before.
+    cache = make_cache(w, reuse_staged=True)
+    n_sets = 3
+    sets = [tuple(dev_bf16(x) for x in wl.chunk_inputs(w, step=s, with_dout=True)) for s in range(n_sets)]
+    q = sets[0][0]
     out = torch.empty_like(q)
     lse = torch.empty((w.batch, w.heads, w.n_q), dtype=torch.float32, device=dev)
     dq, dk_, dv_ = (torch.empty(q.shape, dtype=torch.float32, device=dev) for _ in range(3))
@@ -105,27 +111,33 @@ def main() -> int:
     ws = torch.empty(max(fwd_b, bwd_b), dtype=torch.uint8, device=dev)
     Fc = w.chunk_frames
 
-    def step():
+    def step(i):
+        q, k, v, do = sets[i % n_sets]
         A.astro_chunk_attn_fwd(cache, q, k, v, Fc, out, lse, ws)
         A.astro_chunk_attn_bwd(cache, q, k, v, out, lse, do, Fc, dq, dk_, dv_, ws)
         A.astro_kvcache_append(cache, k, v, Fc)
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    marks[0].record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        marks[i + 1].record()   # on the stream the library launches on (torch's current stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = per_step_ms[len(per_step_ms) // 2] if args.steps % 2 else 0.5 * (per_step_ms[args.steps // 2 - 1] + per_step_ms[args.steps // 2])
     step_flops = flops_fwd(w) + flops_bwd(w)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel HIP-event timing over the same step (separate pass) ------------
     A.astro_profile_begin()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(i)
     ktimes = A.astro_profile_end()
     kernels = {}
     for name, (launches, total_ms) in ktimes.items():
@@ -142,23 +154,26 @@ def main() -> int:
     dominant = max((n for n in ktimes if kernel_flops(n, w)), key=lambda n: ktimes[n][1])
     d_avg = ktimes[dominant][1] / ktimes[dominant][0]
     achieved = kernel_flops(dominant, w) / (d_avg * 1e-3) / 1e12
-    # HBM bytes per launch of that kernel, from the committed rocprofv3 counter runs of this workload
-    traffic = None
+    # HBM bytes per launch of that kernel: NOT measured by this run (counters need rocprofv3); taken
+    # from the committed summary of the rocprofv3 --pmc runs of this command, and labelled as such
+    traffic, traffic_source = None, None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic_rl_bwd.json")) as f:
-            ent = json.load(f)["kernels"].get(dominant) if args.workload == "rl_bwd" else None
+            prof = json.load(f)
+        ent = prof["kernels"].get(dominant) if args.workload == "rl_bwd" else None
         if ent:
             traffic = ent["fetch_bytes"] + ent["write_bytes"]
+            traffic_source = "profiles/hbm_traffic_rl_bwd.json: " + prof.get("source", "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
     except (OSError, ValueError, KeyError):
         pass
     roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
-                "avg_launch_ms": round(d_avg, 4)}
+                "traffic_source": traffic_source, "avg_launch_ms": round(d_avg, 4)}
 
     result = {
         "metric": "chunk-attn fwd+bwd TFLOP/s (algorithmic flops, bf16 MFMA, fp32 accumulate)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "median_ms_per_step": round(median_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B{w.batch} H{w.heads} D{w.head_dim} T{w.tokens_per_frame} "
                                f"ring {w.capacity_frames} frames full, chunk {w.chunk_frames} frames "
@@ -168,7 +183,7 @@ def main() -> int:
         "kernels": kernels,
     }
     cache.close()
-    del q, k, v, do, out, lse, dq, dk_, dv_, ws
+    del q, sets, out, lse, dq, dk_, dv_, ws
 
     # ---- extras: forward-only shapes and the append at batch 8 ----------------------
     if not args.no_extras:

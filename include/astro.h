@@ -66,6 +66,7 @@ extern "C" {
 /* desc.flags */
 #define ASTRO_FLAG_HOST_ONLY 1 /* no device work at all: the handle only plans slots  */
 #define ASTRO_FLAG_WINDOW_RELATIVE 2 /* temporal rotary positions by rank in the window   */
+#define ASTRO_FLAG_REUSE_STAGED 4 /* a backward may reuse what the forward before it staged */
 
 #define ASTRO_MAX_BATCH 64
 #define ASTRO_MAX_CAPACITY_FRAMES 256
@@ -164,7 +165,13 @@ int astro_chunk_attn_fwd(astro_kvcache_t *cache, const void *q, const void *k_ch
  * [B, n_frames*T, H, D], w.r.t. the UN-rotated inputs).  Cached keys / values get
  * no gradient.  q, k_chunk, v_chunk, out, lse must be those of a forward call on
  * the same cache state.  dout has the cache dtype.
- * workspace: device, >= bwd_bytes, 256-byte aligned. */
+ * workspace: device, >= bwd_bytes, 256-byte aligned.
+ * With ASTRO_FLAG_REUSE_STAGED (the re-forward + backward of gradient checkpointing, Table S1):
+ * an attention call whose q, k_chunk, workspace pointer, n_frames and group equal those of the
+ * handle's previous attention call, with no reset or append in between, skips the rotation
+ * pre-pass and reads the rotated copies that call left at the start of the workspace.  The
+ * caller promises that q, k_chunk and the workspace were not written in between (by anything
+ * but this library's attention calls on this handle). */
 int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
                          const void *v_chunk, const void *out, const float *lse,
                          const void *dout, int32_t n_frames, float *dq, float *dk_chunk,

@@ -284,14 +284,17 @@ class RollingCacheOracle:
 
     # -- forward ---------------------------------------------------------------
     def attn_fwd(self, q, k_chunk, v_chunk, n_frames: int, streams=None, heads=None,
-                 return_probs: bool = False):
+                 return_probs: bool = False, rows=None):
         """O [B,Nq,H,D], LSE [B,H,Nq]; only the listed (stream, head) pairs are
-        filled when `streams` / `heads` are given (the rest stay NaN)."""
+        filled when `streams` / `heads` are given (the rest stay NaN).  `rows`: only
+        these query rows are computed (a query's output depends on no other query),
+        against all the keys it sees; the other rows stay NaN."""
         Nq = n_frames * self.T
         assert q.shape == k_chunk.shape == v_chunk.shape == (self.B, Nq, self.H, self.D)
         out = np.full((self.B, Nq, self.H, self.D), np.nan)
         lse = np.full((self.B, self.H, Nq), np.nan)
         probs = {}
+        sel = slice(None) if rows is None else np.asarray(rows, dtype=np.int64)
         for b, h in self._pairs(streams, heads):
             phi = self._chunk_phi(b, n_frames)
             qt = rope_rotate(np.asarray(q[b, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
@@ -299,9 +302,10 @@ class RollingCacheOracle:
             kh, vh = self._context(b, h)
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[b, :, h, :], dtype=np.float64)], 0)
-            p, o, l = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
-            out[b, :, h, :] = o
-            lse[b, h, :] = l
+            vis = self._visible(kh.shape[0], n_frames)
+            p, o, l = _softmax_attention(qt[sel], kt, vv, None if vis is None else vis[sel])
+            out[b, sel, h, :] = o
+            lse[b, h, sel] = l
             if return_probs:
                 probs[(b, h)] = p
         if return_probs:
@@ -358,13 +362,16 @@ class RollingCacheOracle:
         hs = range(self.H) if heads is None else heads
         return [(c, h) for c in cs for h in hs]
 
-    def group_attn_fwd(self, q, k_chunk, v_chunk, n_frames: int, group: int, candidates=None, heads=None):
-        """O [B*G,Nq,H,D], LSE [B*G,H,Nq]; unlisted (candidate, head) pairs stay NaN."""
+    def group_attn_fwd(self, q, k_chunk, v_chunk, n_frames: int, group: int, candidates=None, heads=None,
+                       rows=None):
+        """O [B*G,Nq,H,D], LSE [B*G,H,Nq]; unlisted (candidate, head) pairs stay NaN, and with
+        `rows` only those query rows are computed (as in attn_fwd)."""
         Nq = n_frames * self.T
         assert group >= 1
         assert q.shape == k_chunk.shape == v_chunk.shape == (self.B * group, Nq, self.H, self.D)
         out = np.full((self.B * group, Nq, self.H, self.D), np.nan)
         lse = np.full((self.B * group, self.H, Nq), np.nan)
+        sel = slice(None) if rows is None else np.asarray(rows, dtype=np.int64)
         context = {}
         for c, h in self._candidate_pairs(group, candidates, heads):
             b = c // group
@@ -376,9 +383,10 @@ class RollingCacheOracle:
             kc = rope_rotate(np.asarray(k_chunk[c, :, h:h + 1, :], dtype=np.float64), phi)[:, 0]
             kt = np.concatenate([kh, kc], 0)
             vv = np.concatenate([vh, np.asarray(v_chunk[c, :, h, :], dtype=np.float64)], 0)
-            _, o, l = _softmax_attention(qt, kt, vv, self._visible(kh.shape[0], n_frames))
-            out[c, :, h, :] = o
-            lse[c, h, :] = l
+            vis = self._visible(kh.shape[0], n_frames)
+            _, o, l = _softmax_attention(qt[sel], kt, vv, None if vis is None else vis[sel])
+            out[c, sel, h, :] = o
+            lse[c, h, sel] = l
         return out, lse
 
     def group_attn_bwd(self, q, k_chunk, v_chunk, dout, n_frames: int, group: int, candidates=None, heads=None):

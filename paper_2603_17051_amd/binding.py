@@ -24,6 +24,7 @@ ASTRO_BF16 = 0
 ASTRO_F32 = 1
 ASTRO_FLAG_HOST_ONLY = 1
 ASTRO_FLAG_WINDOW_RELATIVE = 2
+ASTRO_FLAG_REUSE_STAGED = 4
 ASTRO_MAX_BATCH = 64
 ASTRO_MAX_CAPACITY_FRAMES = 256
 
@@ -185,9 +186,10 @@ class KVCache:
 
 def astro_kvcache_create(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
                          rope_pairs=(0, 0, 0), rope_base=10000.0, dtype=ASTRO_BF16, host_only=False,
-                         device="cuda:0", block_frames=0, window_relative=False) -> KVCache:
+                         device="cuda:0", block_frames=0, window_relative=False, reuse_staged=False) -> KVCache:
     """Allocate the K/V storage with torch (unless host_only) and create the handle."""
-    flags = (ASTRO_FLAG_HOST_ONLY if host_only else 0) | (ASTRO_FLAG_WINDOW_RELATIVE if window_relative else 0)
+    flags = ((ASTRO_FLAG_HOST_ONLY if host_only else 0) | (ASTRO_FLAG_WINDOW_RELATIVE if window_relative else 0)
+             | (ASTRO_FLAG_REUSE_STAGED if reuse_staged else 0))
     desc = make_desc(batch, heads, head_dim, grid_h, grid_w, capacity_frames, sink_frames, max_chunk_frames,
                      rope_pairs, rope_base, dtype, flags, block_frames=block_frames)
     k_storage = v_storage = k_sink_storage = None

@@ -25,6 +25,17 @@ struct astro_kvcache {
   float2* d_tab_w = nullptr;
   int device = -1;
   int n_cus = 256;
+  // What the last rotation pre-pass left in a caller's workspace (ASTRO_FLAG_REUSE_STAGED): the
+  // call's chunk pointers, workspace, sizes and the state of the tables it was made in.
+  struct Staged {
+    const void* q = nullptr;
+    const void* k = nullptr;
+    const void* ws = nullptr;
+    int n_frames = 0, group = 0;
+    uint64_t epoch = 0;
+    bool valid = false;
+  } staged;
+  uint64_t epoch = 0;  // bumped by every reset and append: chunk positions may have changed
   astro_kvcache(const RingGeometry& g, void* k, void* v) : geo(g), tables(g.B, g.C, g.S), k_storage(k), v_storage(v) {}
 };
 
@@ -47,7 +58,7 @@ DevGeom dev_geom(const astro_kvcache* c, int group = 1) {
 }
 
 struct Workspace {
-  size_t q_rot, kc_rot, dq_rot, dk_rot, scratch, dk_hist_rot, total;
+  size_t q_rot, kc_rot, tab_t, staged_end, dq_rot, dk_rot, scratch, dk_hist_rot, total;
 };
 
 Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group, bool ring_grads = false) {
@@ -58,9 +69,15 @@ Workspace carve(const astro_kvcache* c, int n_frames, bool bwd, int group, bool 
   const DevGeom d = dev_geom(c, group);
   Workspace w{};
   size_t off = 0;
+  // what the rotation pre-pass leaves: the same bytes at the same offsets for a forward and a
+  // backward of the same chunk size, so a backward can pick up what a forward staged
   w.q_rot = off; off += rot;
   w.kc_rot = off; off += rot;
-  if (bwd) {
+  w.tab_t = off; off += align256((size_t)g.B * group * n_frames * (g.n_t > 0 ? g.n_t : 1) * sizeof(float2));
+  w.staged_end = off;
+  // rotated-frame gradients: the fp32 path turns them back in a pass of its own, the bf16
+  // kernels do it in their epilogues
+  if (bwd && g.dtype == ASTRO_F32) {
     w.dq_rot = off; off += grad;
     w.dk_rot = off; off += grad;
   }
@@ -117,6 +134,7 @@ AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w,
   op.v_chunk = v_chunk;
   op.k_cache = c->k_storage;
   op.v_cache = c->v_storage;
+  op.tab_t = (const float2*)(ws + w.tab_t);
   op.Nq = n_frames * c->geo.T;
   op.group = group;
   // a block size that covers the chunk is no mask at all
@@ -126,13 +144,22 @@ AttnOperands attn_operands(const astro_kvcache* c, char* ws, const Workspace& w,
   return op;
 }
 
-// rotate Q and K_chunk into the workspace (head-major)
-hipError_t stage_chunk(const astro_kvcache* c, const void* q, const void* k_chunk, char* ws, const Workspace& w,
+// rotate Q and K_chunk into the workspace (head-major), unless the handle may reuse staged copies
+// and the last pre-pass was made for exactly this call's chunk, workspace and table state
+hipError_t stage_chunk(astro_kvcache* c, const void* q, const void* k_chunk, char* ws, const Workspace& w,
                        int n_frames, int group, hipStream_t stream) {
+  astro_kvcache::Staged& st = c->staged;
+  if (c->geo.reuse_staged && st.valid && st.q == q && st.k == k_chunk && st.ws == ws && st.n_frames == n_frames &&
+      st.group == group && st.epoch == c->epoch)
+    return hipSuccess;
+  st.valid = false;
   StreamInts first, next;
   stream_ints(c, &first, &next, nullptr, group);
   ScatterDst dst{ws + w.q_rot, ws + w.kc_rot, (int64_t)n_frames * c->geo.T, 0};
-  return launch_rope_scatter(dev_geom(c, group), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next, stream);
+  const hipError_t e = launch_rope_scatter(dev_geom(c, group), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next,
+                                           (float2*)(ws + w.tab_t), stream);
+  if (e == hipSuccess) st = astro_kvcache::Staged{q, k_chunk, ws, n_frames, group, c->epoch, true};
+  return e;
 }
 
 }  // namespace
@@ -219,6 +246,7 @@ int astro_kvcache_reset(astro_kvcache_t* cache, int32_t stream, int32_t start_fr
   if (!cache) return ASTRO_ERR_INVALID_ARG;
   if (stream < -1 || stream >= cache->geo.B || start_frame < 0) return ASTRO_ERR_INVALID_ARG;
   cache->tables.reset(stream, start_frame);
+  ++cache->epoch;
   return ASTRO_OK;
 }
 
@@ -233,7 +261,7 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
     stream_ints(cache, &first, &next, nullptr);
     ScatterDst dst{cache->k_storage, cache->v_storage, (int64_t)g.C * g.T, 1};
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next, stream) != hipSuccess)
+    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next, nullptr, stream) != hipSuccess)
       return ASTRO_ERR_HIP;
     if (g.sinks_move()) {
       // Window-relative positions.  (1) Sink frames that arrive in this call: keep their keys
@@ -267,6 +295,7 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
     }
   }
   cache->tables.append(n_frames);
+  ++cache->epoch;
   return ASTRO_OK;
 }
 
@@ -328,15 +357,15 @@ int astro_group_attn_bwd(astro_kvcache_t* cache, const void* q, const void* k_ch
   if (stage_chunk(cache, q, k_chunk, ws, w, n_frames, group, stream) != hipSuccess) return ASTRO_ERR_HIP;
   const AttnOperands op = attn_operands(cache, ws, w, v_chunk, n_frames, group);
   const DevGeom d = dev_geom(cache, group);
+  if (cache->geo.dtype == ASTRO_BF16)  // gradients leave the kernels un-rotated and token-major
+    return launch_attn_bwd_bf16(d, op, out, lse, dout, dq, dk_chunk, dv_chunk, ws + w.scratch, stream) == hipSuccess
+               ? ASTRO_OK
+               : ASTRO_ERR_HIP;
   float* dq_rot = (float*)(ws + w.dq_rot);
   float* dk_rot = (float*)(ws + w.dk_rot);
-  hipError_t e;
-  if (cache->geo.dtype == ASTRO_F32)
-    e = launch_attn_bwd_f32(d, op, (const float*)out, lse, (const float*)dout, dq_rot, dk_rot, dv_chunk,
-                            (float*)(ws + w.scratch), stream);
-  else
-    e = launch_attn_bwd_bf16(d, op, out, lse, dout, dq_rot, dk_rot, dv_chunk, ws + w.scratch, stream);
-  if (e != hipSuccess) return ASTRO_ERR_HIP;
+  if (launch_attn_bwd_f32(d, op, (const float*)out, lse, (const float*)dout, dq_rot, dk_rot, dv_chunk,
+                          (float*)(ws + w.scratch), stream) != hipSuccess)
+    return ASTRO_ERR_HIP;
   // gradients w.r.t. the un-rotated Q and K_chunk: inverse rotation, back to token-major
   StreamInts first;
   stream_ints(cache, &first, nullptr, nullptr, group);

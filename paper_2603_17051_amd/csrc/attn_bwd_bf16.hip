@@ -34,9 +34,10 @@ struct BwdParams {
   const float* lse;
   float* delta;   // [B][H][Nq]  -<dO, O>
   float* lse2;    // [B][H][Nq]  -LSE * log2(e), written next to delta by the dQ kernel
-  float* dq_rot;  // [B][H][Nq][D]
-  float* dk_rot;  // [B][H][Nq][D]
+  float* dq;      // [B, Nq, H, D]  w.r.t. the un-rotated queries
+  float* dk;      // [B, Nq, H, D]  w.r.t. the un-rotated chunk keys
   float* dv;      // [B, Nq, H, D]
+  RotaryTables rot;
   float* dk_hist_rot;  // [B][H][C*T][D]   (only when hist_keys)
   float* dv_hist;      // [B, C*T, H, D]
   int hist_keys;       // dK/dV kernel: 0 = the chunk's keys, 1 = the resident ring rows (group must be 1)
@@ -282,16 +283,19 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
     if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
   }
 
+  // dQ~ -> dQ: the rotation is turned back here (each lane holds both halves of its pairs), so the
+  // gradient goes out once, token-major, instead of through a rotated fp32 copy and another pass
+  const bool rope = p.rot.n_t + p.rot.n_h + p.rot.n_w != 0;
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     const int q = q0 + 16 * qs;
     if (q < p.Nq) {
-      float* row = p.dq_rot + (bh * p.Nq + q) * D;
+      float* row = p.dq + (((int64_t)b * p.Nq + q) * p.H + h) * D;
+      const TokenTables tt = token_tables(p.rot, b, q);
 #pragma unroll
       for (int dt = 0; dt < Wave::DT; ++dt) {
-        f32x4 x;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) x[c] = w.dq[dt][qs][c] * p.scale;
+        f32x4 x = w.dq[dt][qs] * p.scale;
+        if (rope) x = unrotate_quad(p.rot, tt, 4 * dt + g, x);
         *reinterpret_cast<f32x4*>(row + 16 * dt + 4 * g) = x;
       }
     }
@@ -565,25 +569,29 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
     if (++n > ntiles) break;
   }
 
+  // dV as it is; dK~ of chunk keys is turned back to dK here (ring rows keep the rotated frame:
+  // the frame a slot holds is looked up by the pass that follows)
+  const bool rope = kKey && !p.hist_keys && p.rot.n_t + p.rot.n_h + p.rot.n_w != 0;
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int j = jc + 16 * ks;
     if (j >= n_keys) continue;
     float* row;
     if constexpr (kKey)
-      row = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + j) * D : p.dk_rot + (bh * p.Nq + j) * D;
+      row = p.hist_keys ? p.dk_hist_rot + (bh * p.cache_rows + j) * D : p.dk + (((int64_t)b * p.Nq + j) * p.H + h) * D;
     else
       row = p.hist_keys ? p.dv_hist + (((int64_t)b * p.cache_rows + j) * p.H + h) * D
                         : p.dv + (((int64_t)b * p.Nq + j) * p.H + h) * D;
+    TokenTables tt{};
+    if (rope) tt = token_tables(p.rot, b, j);
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
       f32x4 x;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if constexpr (kKey)
-          x[c] = w.dk[dt][ks][c] * p.scale;
-        else
-          x[c] = w.dv[dt][ks][c];
+      if constexpr (kKey) {
+        x = w.dk[dt][ks] * p.scale;
+        if (rope) x = unrotate_quad(p.rot, tt, 4 * dt + g, x);
+      } else {
+        x = w.dv[dt][ks];
       }
       *reinterpret_cast<f32x4*>(row + 16 * dt + 4 * g) = x;
     }
@@ -608,7 +616,7 @@ __global__ void __launch_bounds__(kPairThreads, 1) attn_bwd_dkv_kernel(BwdParams
 
 template <int D>
 BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
-                      float* dq_rot, float* dk_rot, float* dv, void* scratch) {
+                      float* dq, float* dk, float* dv, void* scratch) {
   BwdParams p;
   p.q_rot = (const __bf16*)op.q_rot;
   p.kc_rot = (const __bf16*)op.kc_rot;
@@ -620,9 +628,10 @@ BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out,
   p.lse = lse;
   p.delta = (float*)scratch;
   p.lse2 = p.delta + (size_t)g.B * g.H * op.Nq;
-  p.dq_rot = dq_rot;
-  p.dk_rot = dk_rot;
+  p.dq = dq;
+  p.dk = dk;
   p.dv = dv;
+  p.rot = RotaryTables{op.tab_t, g.tab_h, g.tab_w, g.n_t, g.n_h, g.n_w, g.gw, g.T, op.Nq / g.T};
   p.H = g.H;
   p.BH = g.B * g.H;
   p.tiles = 0;
@@ -641,8 +650,8 @@ BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out,
 
 template <int D>
 hipError_t launch(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse, const void* dout,
-                  float* dq_rot, float* dk_rot, float* dv, void* scratch, hipStream_t stream) {
-  BwdParams p = make_params<D>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch);
+                  float* dq, float* dk, float* dv, void* scratch, hipStream_t stream) {
+  BwdParams p = make_params<D>(g, op, out, lse, dout, dq, dk, dv, scratch);
   {
     ProfileScope prof("attn_bwd_dq_bf16", stream);
     const int qtile = kDqWaves * 32;
@@ -688,10 +697,10 @@ hipError_t launch_attn_bwd_hist_bf16(const DevGeom& g, const AttnOperands& op, c
 size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq) { return 2 * (size_t)g.B * g.H * Nq * sizeof(float); }
 
 hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out, const float* lse,
-                                const void* dout, float* dq_rot, float* dk_rot, float* dv, void* scratch,
+                                const void* dout, float* dq, float* dk, float* dv, void* scratch,
                                 hipStream_t stream) {
-  if (g.D == 128) return launch<128>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch, stream);
-  return launch<64>(g, op, out, lse, dout, dq_rot, dk_rot, dv, scratch, stream);
+  if (g.D == 128) return launch<128>(g, op, out, lse, dout, dq, dk, dv, scratch, stream);
+  return launch<64>(g, op, out, lse, dout, dq, dk, dv, scratch, stream);
 }
 
 }  // namespace astro

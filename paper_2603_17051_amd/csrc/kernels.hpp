@@ -51,10 +51,12 @@ struct ScatterDst {
 // a_in, b_in: [B, n_frames*T, H, D].  a is always rotated (if the geometry has rotary
 // pairs); b is rotated iff rotate_b.  first_frame.v[b] = absolute index of the chunk's
 // first frame, next_n.v[b] = its stream-local number.
+// tab_t_out (may be null): [B][n_frames][n_t] (cos, sin) of the temporal pairs at each chunk frame's
+// position, exactly the values this launch rotates with, for the kernels that rotate gradients back.
 hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in,
                                ScatterDst dst, bool rotate_b, int n_frames,
                                const StreamInts& first_frame, const StreamInts& next_n,
-                               hipStream_t stream);
+                               float2* tab_t_out, hipStream_t stream);
 
 // Inverse rotation of fp32 gradients: src head-major [B][H][n_frames*T][D] (rotated frame)
 // -> dst [B, n_frames*T, H, D] (un-rotated frame).
@@ -87,6 +89,7 @@ struct AttnOperands {
   const void* v_chunk;  // [B, Nq, H, D] caller's chunk values
   const void* k_cache;  // [B][H][C*T][D]
   const void* v_cache;  // [B][H][C*T][D]
+  const float2* tab_t;  // [B][n_frames][n_t] (cos, sin) of the temporal pairs at the chunk's frames (workspace)
   int Nq;
   int group;             // candidates per cache stream (1 = plain chunk attention)
   int block_rows;        // causal block inside the chunk, in token rows; 0 = none (whole chunk)
@@ -110,8 +113,10 @@ int bf16_fwd_splits(const DevGeom& g, const AttnOperands& op, bool have_parts);
 hipError_t launch_attn_fwd_bf16(const DevGeom& g, const AttnOperands& op, void* out, float* lse, void* parts,
                                 hipStream_t stream);
 size_t bf16_bwd_workspace_bytes(const DevGeom& g, int Nq);  // beyond q_rot / kc_rot
+// dq, dk, dv: [B, Nq, H, D] fp32 w.r.t. the UN-rotated inputs (the kernels turn dQ~ and dK~ back in
+// their epilogues with the tables of `g` and op.tab_t)
 hipError_t launch_attn_bwd_bf16(const DevGeom& g, const AttnOperands& op, const void* out,
-                                const float* lse, const void* dout, float* dq_rot, float* dk_rot,
+                                const float* lse, const void* dout, float* dq, float* dk,
                                 float* dv, void* scratch, hipStream_t stream);
 // Gradients of the ring rows (the non-detached backward): dk_hist_rot [B][H][C*T][D] w.r.t. the
 // rotated keys as cached, dv_hist [B, C*T, H, D]; rows of empty slots are not written.  Needs

@@ -223,6 +223,37 @@ __device__ __forceinline__ int first_query_row_seeing(int j, int block_rows) {
   return block_rows == 0 ? 0 : (j / block_rows) * block_rows;
 }
 
+// ---- turning a gradient w.r.t. rotated queries / keys back in an epilogue ---------------------
+// The rotary tables of one call: (cos, sin) per temporal pair and chunk frame of each candidate
+// (written by the rotation pre-pass, so they are the values the operands were rotated with), per
+// row and per column.  All counts 0 = no rotary embedding.
+struct RotaryTables {
+  const float2* tab_t;  // [B][n_frames][n_t]
+  const float2* tab_h;  // [gh][n_h]
+  const float2* tab_w;  // [gw][n_w]
+  int n_t, n_h, n_w, gw, T, n_frames;
+};
+// Position of chunk token `tok` of candidate b, as the three table rows of its pairs.
+struct TokenTables {
+  const float2 *t, *h, *w;
+};
+__device__ __forceinline__ TokenTables token_tables(const RotaryTables& r, int b, int tok) {
+  const int fi = tok / r.T, rem = tok - fi * r.T;
+  const int row = rem / r.gw, col = rem - row * r.gw;
+  return TokenTables{r.tab_t + ((int64_t)b * r.n_frames + fi) * r.n_t, r.tab_h + row * r.n_h, r.tab_w + col * r.n_w};
+}
+__device__ __forceinline__ float2 pair_cos_sin(const RotaryTables& r, const TokenTables& t, int pair) {
+  if (pair < r.n_t) return t.t[pair];
+  pair -= r.n_t;
+  return pair < r.n_h ? t.h[pair] : t.w[pair - r.n_h];
+}
+// x = four consecutive components 4*quad .. 4*quad+3 (two adjacent pairs) of a gradient w.r.t. the
+// rotated vector; returns them w.r.t. the un-rotated one: R(phi)^T applied to each pair.
+__device__ __forceinline__ f32x4 unrotate_quad(const RotaryTables& r, const TokenTables& t, int quad, f32x4 x) {
+  const float2 a = pair_cos_sin(r, t, 2 * quad), b = pair_cos_sin(r, t, 2 * quad + 1);
+  return f32x4{x[0] * a.x + x[1] * a.y, x[1] * a.x - x[0] * a.y, x[2] * b.x + x[3] * b.y, x[3] * b.x - x[2] * b.y};
+}
+
 // wait until this wave's outstanding global loads (including direct-to-LDS ones) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 // ... all but the N most recently issued ones (loads complete in issue order)

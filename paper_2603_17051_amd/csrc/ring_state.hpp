@@ -17,6 +17,7 @@ struct RingGeometry {
   int dtype;
   bool host_only;
   bool window_relative;  // temporal positions by rank in the attended sequence
+  bool reuse_staged;     // a backward may pick up the rotated Q / K_chunk the forward before it staged
   double rope_base;
   size_t elem_bytes() const { return dtype == ASTRO_BF16 ? 2 : 4; }
   size_t rows_per_head() const { return (size_t)C * (size_t)T; }
@@ -43,7 +44,7 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   if (npairs != 0 && npairs != d->head_dim / 2) return ASTRO_ERR_INVALID_ARG;
   if (npairs != 0 && !(d->rope_base > 1.0)) return ASTRO_ERR_INVALID_ARG;
   if (d->dtype != ASTRO_BF16 && d->dtype != ASTRO_F32) return ASTRO_ERR_UNSUPPORTED;
-  if (d->flags & ~(ASTRO_FLAG_HOST_ONLY | ASTRO_FLAG_WINDOW_RELATIVE)) return ASTRO_ERR_INVALID_ARG;
+  if (d->flags & ~(ASTRO_FLAG_HOST_ONLY | ASTRO_FLAG_WINDOW_RELATIVE | ASTRO_FLAG_REUSE_STAGED)) return ASTRO_ERR_INVALID_ARG;
   if (d->block_frames < 0) return ASTRO_ERR_INVALID_ARG;
   const bool host_only = (d->flags & ASTRO_FLAG_HOST_ONLY) != 0;
   if (!host_only && (!d->k_storage || !d->v_storage)) return ASTRO_ERR_INVALID_ARG;
@@ -60,6 +61,7 @@ inline int validate_desc(const astro_kvcache_desc_t* d, RingGeometry* g) {
   g->n_t = d->rope_pairs_t; g->n_h = d->rope_pairs_h; g->n_w = d->rope_pairs_w;
   g->dtype = d->dtype; g->host_only = host_only; g->rope_base = d->rope_base;
   g->window_relative = (d->flags & ASTRO_FLAG_WINDOW_RELATIVE) != 0;
+  g->reuse_staged = (d->flags & ASTRO_FLAG_REUSE_STAGED) != 0;
   return ASTRO_OK;
 }
 

@@ -42,7 +42,8 @@ template <typename Elem, bool kRotateB>
 __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const Elem* __restrict__ a_in,
                                                                 const Elem* __restrict__ b_in, Elem* __restrict__ a_out,
                                                                 Elem* __restrict__ b_out, int64_t rows_per_head, int ring,
-                                                                int n_frames, StreamInts first_frame, StreamInts next_n) {
+                                                                int n_frames, StreamInts first_frame, StreamInts next_n,
+                                                                float2* __restrict__ tab_t_out) {
   constexpr int EPC = 16 / sizeof(Elem);  // elements per 16-byte chunk
   __shared__ float2 tab[kMaxBlockPairs];
   const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
@@ -73,7 +74,12 @@ __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const
           xb[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(b_in + in_off));
         }
       }
-      if (rope && base == 0) fill_block_table(tab, g, first_frame.v[b] + fi, row);
+      if (rope && base == 0) {
+        fill_block_table(tab, g, first_frame.v[b] + fi, row);
+        // one block per (stream, frame) leaves the temporal pairs' (cos, sin) for the backward's epilogues
+        if (tab_t_out && row == 0 && h == 0 && (int)threadIdx.x < g.n_t)
+          tab_t_out[((int64_t)b * n_frames + fi) * g.n_t + threadIdx.x] = tab[threadIdx.x];
+      }
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const int idx = base + u * kThreads + threadIdx.x;
@@ -220,7 +226,7 @@ __global__ void __launch_bounds__(kThreads) rope_sink_rerotate_kernel(DevGeom g,
 
 hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in, ScatterDst dst,
                                bool rotate_b, int n_frames, const StreamInts& first_frame, const StreamInts& next_n,
-                               hipStream_t stream) {
+                               float2* tab_t_out, hipStream_t stream) {
   dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
   ProfileScope prof(dst.ring ? "kv_append_rope" : "chunk_rope_stage", stream);
   if (dtype == ASTRO_BF16) {
@@ -228,19 +234,19 @@ hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, co
     auto b = static_cast<const __bf16*>(b_in);
     if (rotate_b)
       rope_scatter_kernel<__bf16, true><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
-                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
     else
       rope_scatter_kernel<__bf16, false><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
-                                                                    dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+                                                                    dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
   } else {
     auto a = static_cast<const float*>(a_in);
     auto b = static_cast<const float*>(b_in);
     if (rotate_b)
       rope_scatter_kernel<float, true><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
-                                                                  dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+                                                                  dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
     else
       rope_scatter_kernel<float, false><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
-                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n);
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
   }
   return hipGetLastError();
 }

@@ -9,11 +9,21 @@ from oracle import RollingCacheOracle
 
 # contract: max abs error on outputs and gradients for bf16 N(0,1) inputs
 BF16_ABS_TOL = 2e-2
-# the abs bound is larger than the signal at production key counts (outputs have
-# std ~ sqrt(e/Nk)), so errors are also gated relative to the reference's rms
-BF16_MAX_OVER_MAX = 3e-2   # max |err| / max |ref|
-BF16_RMS_OVER_RMS = 1e-2   # rms(err) / rms(ref)
+# The abs bound is larger than the signal at production key counts (outputs have std ~
+# sqrt(e/Nk)), so errors are also gated relative to the reference.  The bounds are 2 x what a
+# CPU model of the kernels' bf16 roundings (tests/bf16_model.py) lands from the fp64 definition on
+# N(0,1) inputs (rms/rms 3.6e-3, max/max 6.9e-3 at the smallest named shape and a mid-size one;
+# tests/test_error_gates.py recomputes them and checks these constants).  The largest error is
+# normalised by the largest reference entry, not by rms(ref): max/rms moves with the SHAPE of the
+# reference's distribution (causal blocks leave late keys with small gradients, which lowers
+# rms(ref) and leaves the largest error where it was: 8.7e-2 on a correct dK against 3.3e-2 on the
+# unmasked case), so no single bound on it is both tight and passable; it is reported only.
+BF16_RMS_OVER_RMS = 7.2e-3   # rms(err) / rms(ref)
+BF16_MAX_OVER_MAX = 1.4e-2   # max |err| / max |ref|
 F32_ABS_TOL = 1e-5
+# inputs outside the N(0,1) contract (large logits, keys with a large common offset): the error
+# may be this many times what the rounding model lands on the SAME inputs
+MODEL_FACTOR = 2.0
 
 
 def dev_bf16(bits: np.ndarray, device="cuda:0"):
@@ -41,13 +51,31 @@ def err_stats(got: np.ndarray, ref: np.ndarray):
     return float(np.abs(e).max()), float(np.abs(e).max() / max_ref), float(np.sqrt(np.mean(e ** 2)) / rms_ref)
 
 
-def assert_bf16_close(got, ref, what: str, report=None, rms_gate=BF16_RMS_OVER_RMS, abs_tol=BF16_ABS_TOL):
+def assert_bf16_close(got, ref, what: str, report=None):
+    """The N(0,1) contract plus the normalised gates."""
     mx, mx_n, rms_n = err_stats(got, ref)
+    mask = np.isfinite(ref)
+    mx_r = mx / float(np.sqrt(np.mean(ref[mask] ** 2)))
     if report is not None:
-        report.append(f"{what}: max_abs={mx:.3e} max/max={mx_n:.3e} rms/rms={rms_n:.3e}")
-    assert mx <= abs_tol, f"{what}: max abs err {mx} > {abs_tol}"
+        report.append(f"{what}: max_abs={mx:.3e} max/max={mx_n:.3e} max/rms={mx_r:.3e} rms/rms={rms_n:.3e}")
+    assert mx <= BF16_ABS_TOL, f"{what}: max abs err {mx} > {BF16_ABS_TOL}"
     assert mx_n <= BF16_MAX_OVER_MAX, f"{what}: max err / max |ref| = {mx_n}"
-    assert rms_n <= rms_gate, f"{what}: rms err / rms(ref) = {rms_n}"
+    assert rms_n <= BF16_RMS_OVER_RMS, f"{what}: rms err / rms(ref) = {rms_n}"
+
+
+def assert_within_model(got, ref, model, what: str, report=None):
+    """For inputs outside the N(0,1) contract: the error against the fp64 reference may be
+    MODEL_FACTOR times the error of the bf16 rounding model on the same inputs (max and rms), plus
+    a floor for what the model leaves out (fp32 accumulation of the products, fp32 exp2)."""
+    assert np.isfinite(got).all(), f"{what}: non-finite values in the GPU result"
+    e, em = got - ref, model - ref
+    floor = 2e-5 * max(1.0, float(np.abs(ref).max()))
+    mx, mx_m = float(np.abs(e).max()), float(np.abs(em).max())
+    rms, rms_m = float(np.sqrt(np.mean(e ** 2))), float(np.sqrt(np.mean(em ** 2)))
+    if report is not None:
+        report.append(f"{what}: max_abs={mx:.3e} (model {mx_m:.3e}) rms={rms:.3e} (model {rms_m:.3e})")
+    assert mx <= MODEL_FACTOR * mx_m + floor, f"{what}: max abs err {mx}, rounding model {mx_m}"
+    assert rms <= MODEL_FACTOR * rms_m + floor, f"{what}: rms err {rms}, rounding model {rms_m}"
 
 
 def assert_f32_close(got, ref, what: str):

@@ -84,3 +84,45 @@ def test_group_shared_prefix_production_shape_sampled_pairs():
         assert_bf16_close(host_f64(gv[c, :, h]), rv[c, :, h], f"candidate {c} head {h} dv", rep)
     _report(rep)
     ls.close()
+
+
+def test_group_shared_prefix_production_shape_every_candidate():
+    """The same 8 candidates over one cache: every (candidate, head) pair of the forward on a
+    sample of query rows, outputs pre-filled with NaN; two pairs in full, forward and backward (a
+    key's gradient needs every query row of its pair)."""
+    import torch
+    w, G = wl.SHARED_PREFIX, 8
+    ls = Lockstep(w, max_chunk=3, start_frames=[13])
+    A = ls.A
+    pk, pv = wl.history_frame_pool(w, 6)
+    _fill_history(ls, w, pk, pv, 18)
+    q, k, v, do = wl.group_inputs(w, G, with_dout=True)
+    q_d, k_d, v_d, do_d = (ls.dev(x) for x in (q, k, v, do))
+    shape = (G, w.n_q, w.heads, w.head_dim)
+    out = torch.full(shape, float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.full((G, w.heads, w.n_q), float("nan"), dtype=torch.float32, device="cuda:0")
+    gq, gk, gv = (torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0") for _ in range(3))
+    A.astro_group_attn_fwd(ls.cache, q_d, k_d, v_d, 3, G, out, lse)
+    A.astro_group_attn_bwd(ls.cache, q_d, k_d, v_d, out, lse, do_d, 3, G, gq, gk, gv)
+    torch.cuda.synchronize()
+    go, gl = host_f64(out), host_f64(lse)
+    for name, t in (("out", go), ("lse", gl), ("dq", host_f64(gq)), ("dk", host_f64(gk)), ("dv", host_f64(gv))):
+        assert np.isfinite(t).all(), f"{name}: elements no workgroup wrote"
+    qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in (q, k, v, do))
+    rng = np.random.Generator(np.random.Philox(key=[w.seed, 777]))
+    rep = []
+    for c in range(G):
+        for h in range(w.heads):
+            rows = np.unique(np.concatenate([[0, 127, 128, w.n_q - 1], rng.integers(0, w.n_q, 124)]))
+            ro, rl = ls.oracle.group_attn_fwd(qf, kf, vf, 3, G, candidates=[c], heads=[h], rows=rows)
+            assert_bf16_close(go[c, rows, h], ro[c, rows, h], f"candidate {c} head {h} out (row sample)", rep)
+            assert_bf16_close(gl[c, h, rows], rl[c, h, rows], f"candidate {c} head {h} lse (row sample)", rep)
+    for c, h in [(3, 0), (7, 8)]:
+        ro, rl = ls.oracle.group_attn_fwd(qf, kf, vf, 3, G, candidates=[c], heads=[h])
+        assert_bf16_close(go[c, :, h], ro[c, :, h], f"candidate {c} head {h} out", rep)
+        rq, rk, rv = ls.oracle.group_attn_bwd(qf, kf, vf, dof, 3, G, candidates=[c], heads=[h])
+        assert_bf16_close(host_f64(gq[c, :, h]), rq[c, :, h], f"candidate {c} head {h} dq", rep)
+        assert_bf16_close(host_f64(gk[c, :, h]), rk[c, :, h], f"candidate {c} head {h} dk", rep)
+        assert_bf16_close(host_f64(gv[c, :, h]), rv[c, :, h], f"candidate {c} head {h} dv", rep)
+    _report(rep[-4:])
+    ls.close()
