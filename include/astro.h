@@ -20,8 +20,15 @@
  *   All launches are asynchronous on the caller's HIP stream (`hip_stream` is a
  *   hipStream_t cast to void*; NULL = the default stream).  Calls on one cache
  *   handle must be made from one host thread at a time.
- *   Every function returns ASTRO_OK (0) or a negative astro error; on error no
- *   state has changed and nothing has been launched.
+ *   Every function returns ASTRO_OK (0) or a negative astro error.  Arguments and state are
+ *   checked before anything else: ASTRO_ERR_INVALID_ARG, _BAD_STATE, _UNSUPPORTED and _WORKSPACE
+ *   mean that nothing was launched and no state has changed.  ASTRO_ERR_HIP means the HIP runtime
+ *   refused a launch or a copy of a call that was valid: launches before it may be enqueued, the
+ *   call's output buffers and workspace contents are undefined, and the tables are not advanced.
+ *   If that happens to astro_kvcache_append after the ring was touched, the ring rows no longer
+ *   match the tables: the handle then answers every call but astro_kvcache_tables and
+ *   astro_kvcache_destroy with ASTRO_ERR_BAD_STATE until astro_kvcache_reset(cache, -1, ...)
+ *   has emptied all streams.
  *
  * Rotary embedding (the paper names none; this layout is fixed by the library):
  *   adjacent pairs (x[2i], x[2i+1]), i < D/2; pairs [0, n_t) turn with the
@@ -234,6 +241,22 @@ int astro_nft_loss(const void *v_theta, const void *v_old, const void *v_ref, co
                    int64_t elems_per_sample, int32_t dtype, float a_max, float beta, float lambda_kl,
                    float *loss, float *grad_v_theta, void *workspace, size_t workspace_bytes,
                    void *hip_stream);
+
+/* astro_nft_loss for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * arguments, results and errors as astro_nft_loss without the workspace: r~, the masked count and
+ * the per-block partial sums live in a static device array of astro_nft_loss_static_bytes() bytes
+ * (1 MiB) that every GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing and calls no allocating routine.  A size whose workspace
+ * (astro_nft_loss_workspace_bytes) exceeds the array is rejected with ASTRO_ERR_WORKSPACE and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams or host threads) race; calls on one stream are ordered and safe, and
+ * no call depends on what an earlier one left in the array. */
+int astro_nft_loss_static_bytes(size_t *bytes);
+int astro_nft_loss_static(const void *v_theta, const void *v_old, const void *v_ref, const void *target,
+                          const float *advantage, const int32_t *kl_mask, int32_t n_samples,
+                          int64_t elems_per_sample, int32_t dtype, float a_max, float beta,
+                          float lambda_kl, float *loss, float *grad_v_theta, void *hip_stream);
 
 /* Measurement aid (Sec. 3.2 / 3.3 name no kernels; this times the library's own):
  * between begin and end every kernel launch is bracketed by HIP events recorded on

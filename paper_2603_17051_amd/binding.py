@@ -33,7 +33,7 @@ EXPORTED = (
     "astro_kvcache_append", "astro_kvcache_tables", "astro_chunk_attn_workspace_bytes",
     "astro_chunk_attn_fwd", "astro_chunk_attn_bwd", "astro_strerror",
     "astro_group_attn_workspace_bytes", "astro_group_attn_fwd", "astro_group_attn_bwd",
-    "astro_nft_loss_workspace_bytes", "astro_nft_loss",
+    "astro_nft_loss_workspace_bytes", "astro_nft_loss", "astro_nft_loss_static_bytes", "astro_nft_loss_static",
     "astro_chunk_attn_bwd_full_workspace_bytes", "astro_chunk_attn_bwd_full",
     "astro_profile_begin", "astro_profile_end", "astro_calib_mfma", "astro_calib_copy",
 )
@@ -88,6 +88,9 @@ def _load() -> ctypes.CDLL:
     lib.astro_nft_loss_workspace_bytes.argtypes = [c_int32, ctypes.c_int64, P(c_size_t)]
     lib.astro_nft_loss.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, ctypes.c_int64,
                                    c_int32, c_float, c_float, c_float, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.astro_nft_loss_static_bytes.argtypes = [P(c_size_t)]
+    lib.astro_nft_loss_static.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, ctypes.c_int64,
+                                          c_int32, c_float, c_float, c_float, c_void_p, c_void_p, c_void_p]
     lib.astro_chunk_attn_bwd_full_workspace_bytes.argtypes = [c_void_p, c_int32, P(c_size_t)]
     lib.astro_chunk_attn_bwd_full.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                               c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -405,6 +408,34 @@ def astro_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, a_max: flo
                                n, elems, dtype, float(a_max), float(beta), float(lambda_kl), _ptr(loss), _ptr(grad),
                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "astro_nft_loss")
+    return loss, grad
+
+
+def astro_nft_loss_static_bytes() -> int:
+    b = c_size_t(0)
+    _check(_lib.astro_nft_loss_static_bytes(byref(b)), "astro_nft_loss_static_bytes")
+    return b.value
+
+
+def astro_nft_loss_static(v_theta, v_old, v_ref, target, advantage, kl_mask, a_max: float, beta: float, lambda_kl: float,
+                          loss, grad, stream=None):
+    """astro_nft_loss without a workspace (the library's static device array is the scratch).  `loss`
+    (fp32 [3]) and `grad` (fp32 like v_theta) are the caller's: the call itself allocates nothing."""
+    n = v_theta.shape[0]
+    elems = v_theta.numel() // n
+    for name, t in (("v_old", v_old), ("v_ref", v_ref), ("target", target)):
+        if t.shape != v_theta.shape or t.dtype != v_theta.dtype or not t.is_contiguous():
+            raise ValueError(f"{name}: must match v_theta in shape and dtype and be contiguous")
+    if v_theta.dtype not in (torch.bfloat16, torch.float32) or not v_theta.is_contiguous():
+        raise ValueError("v_theta: expected contiguous bf16 or fp32")
+    if advantage.dtype != torch.float32 or advantage.numel() != n or kl_mask.dtype != torch.int32 or kl_mask.numel() != n:
+        raise ValueError("advantage: fp32 [n]; kl_mask: int32 [n]")
+    if grad.dtype != torch.float32 or grad.numel() != v_theta.numel() or loss.dtype != torch.float32 or loss.numel() < 3:
+        raise ValueError("grad: fp32 like v_theta; loss: fp32 [3]")
+    dtype = ASTRO_BF16 if v_theta.dtype == torch.bfloat16 else ASTRO_F32
+    _check(_lib.astro_nft_loss_static(_ptr(v_theta), _ptr(v_old), _ptr(v_ref), _ptr(target), _ptr(advantage), _ptr(kl_mask),
+                                      n, elems, dtype, float(a_max), float(beta), float(lambda_kl), _ptr(loss), _ptr(grad),
+                                      _stream(stream)), "astro_nft_loss_static")
     return loss, grad
 
 

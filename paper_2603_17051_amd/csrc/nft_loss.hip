@@ -4,6 +4,8 @@
 // once (4 tensors) and its gradient written once (cache-bypassing loads and stores).  Deterministic: per-block partial sums in a
 // workspace, summed in a fixed order by one block.  Two launches (main, final sum) up to 1024
 // samples, three (prepare, main, final sum) above.
+#include <mutex>
+
 #include "kernels.hpp"
 
 namespace astro {
@@ -184,14 +186,7 @@ __global__ void __launch_bounds__(kThreads) nft_finalize_kernel(NftParams p) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 int blocks_per_sample(int64_t E) { return (int)((E + kElemsPerBlock - 1) / kElemsPerBlock); }
 
-}  // namespace
-}  // namespace astro
-
-using namespace astro;
-
-extern "C" {
-
-int astro_nft_loss_workspace_bytes(int32_t n_samples, int64_t elems_per_sample, size_t* bytes) {
+int workspace_bytes_of(int32_t n_samples, int64_t elems_per_sample, size_t* bytes) {
   if (!bytes || n_samples < 1 || n_samples > 65535 || elems_per_sample < 1 || elems_per_sample > ((int64_t)1 << 40))
     return ASTRO_ERR_INVALID_ARG;
   *bytes = align256((size_t)n_samples * sizeof(float)) + 256 +
@@ -199,12 +194,14 @@ int astro_nft_loss_workspace_bytes(int32_t n_samples, int64_t elems_per_sample, 
   return ASTRO_OK;
 }
 
-int astro_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, const void* target, const float* advantage,
-                   const int32_t* kl_mask, int32_t n_samples, int64_t elems_per_sample, int32_t dtype, float a_max,
-                   float beta, float lambda_kl, float* loss, float* grad_v_theta, void* workspace, size_t workspace_bytes,
-                   void* hip_stream) {
+// Validation and launches shared by the two entry points; `workspace` is device memory of at
+// least the bytes workspace_bytes_of() reports (the caller's, or the static array below).
+int run_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, const void* target, const float* advantage,
+                 const int32_t* kl_mask, int32_t n_samples, int64_t elems_per_sample, int32_t dtype, float a_max,
+                 float beta, float lambda_kl, float* loss, float* grad_v_theta, void* workspace, size_t workspace_bytes,
+                 hipStream_t stream) {
   size_t need = 0;
-  if (astro_nft_loss_workspace_bytes(n_samples, elems_per_sample, &need) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
+  if (workspace_bytes_of(n_samples, elems_per_sample, &need) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
   if (!v_theta || !v_old || !v_ref || !target || !advantage || !kl_mask || !loss || !grad_v_theta) return ASTRO_ERR_INVALID_ARG;
   if (dtype != ASTRO_BF16 && dtype != ASTRO_F32) return ASTRO_ERR_INVALID_ARG;
   if (!(a_max > 0.f) || !(beta == beta) || !(lambda_kl == lambda_kl)) return ASTRO_ERR_INVALID_ARG;
@@ -227,7 +224,6 @@ int astro_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, co
   p.blocks_per_sample = blocks_per_sample(elems_per_sample);
   p.E = elems_per_sample;
   p.inv_a_max = 1.f / a_max; p.beta = beta; p.lambda_kl = lambda_kl;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   {
     ProfileScope prof("nft_loss", stream);
     const dim3 grid(p.blocks_per_sample, n_samples);
@@ -246,6 +242,73 @@ int astro_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, co
     nft_finalize_kernel<<<1, kThreads, 0, stream>>>(p);
   }
   return hipGetLastError() == hipSuccess ? ASTRO_OK : ASTRO_ERR_HIP;
+}
+
+// ---- the entry point that allocates nothing -------------------------------------------------
+// r~, the masked count and the per-block partial sums live in a file-scope device array instead
+// of a caller's workspace.  Every GPU the library runs on holds its own copy of the array at its
+// own address for the life of the process; the host-side name of the array is not that address,
+// so the address is asked for once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return ASTRO_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return ASTRO_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return ASTRO_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return ASTRO_OK;
+}
+
+}  // namespace
+}  // namespace astro
+
+using namespace astro;
+
+extern "C" {
+
+int astro_nft_loss_workspace_bytes(int32_t n_samples, int64_t elems_per_sample, size_t* bytes) {
+  return workspace_bytes_of(n_samples, elems_per_sample, bytes);
+}
+
+int astro_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, const void* target, const float* advantage,
+                   const int32_t* kl_mask, int32_t n_samples, int64_t elems_per_sample, int32_t dtype, float a_max,
+                   float beta, float lambda_kl, float* loss, float* grad_v_theta, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  return run_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, n_samples, elems_per_sample, dtype, a_max, beta,
+                      lambda_kl, loss, grad_v_theta, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int astro_nft_loss_static_bytes(size_t* bytes) {
+  if (!bytes) return ASTRO_ERR_INVALID_ARG;
+  *bytes = kStaticScratchBytes;
+  return ASTRO_OK;
+}
+
+int astro_nft_loss_static(const void* v_theta, const void* v_old, const void* v_ref, const void* target,
+                          const float* advantage, const int32_t* kl_mask, int32_t n_samples, int64_t elems_per_sample,
+                          int32_t dtype, float a_max, float beta, float lambda_kl, float* loss, float* grad_v_theta,
+                          void* hip_stream) {
+  size_t need = 0;
+  if (workspace_bytes_of(n_samples, elems_per_sample, &need) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
+  if (need > kStaticScratchBytes) return ASTRO_ERR_WORKSPACE;  // more partial sums than the static array holds
+  void* ws = nullptr;
+  const int rc = static_scratch_of_current_device(&ws);
+  if (rc != ASTRO_OK) return rc;
+  return run_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, n_samples, elems_per_sample, dtype, a_max, beta,
+                      lambda_kl, loss, grad_v_theta, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"
