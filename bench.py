@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="rl_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-full", action="store_true",
+                    help="time the oracle on the WHOLE step (every stream and head) instead of the bounded sample")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-calibration", action="store_true")
     args = ap.parse_args()
@@ -223,6 +225,27 @@ def main() -> int:
             extras[name] = ent
             ce.close()
             del qe, ke, ve, oe, le, wse
+        # the batch-1 forward with frame-by-frame causality inside the chunk: 444 workgroups, split over the keys
+        we = wl.WORKLOADS["prod_fwd"]
+        ce = make_cache(we, block_frames=1)
+        qe, ke, ve = (dev_bf16(x) for x in wl.chunk_inputs(we))
+        oe = torch.empty_like(qe)
+        le = torch.empty((we.batch, we.heads, we.n_q), dtype=torch.float32, device=dev)
+        wse = torch.empty(A.astro_chunk_attn_workspace_bytes(ce, we.chunk_frames)[0], dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            A.astro_chunk_attn_fwd(ce, qe, ke, ve, we.chunk_frames, oe, le, wse)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 20
+        T_, Fc_ = we.tokens_per_frame, we.chunk_frames
+        fl = 4.0 * (we.n_q * (we.n_k - we.n_q) + T_ * T_ * Fc_ * (Fc_ + 1) / 2.0) * we.head_dim * we.heads * we.batch
+        extras["prod_fwd_frame_causal"] = {"fwd_ms": round(ms, 4), "fwd_tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+                                           "frac_bf16_mfma_peak": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)}
+        ce.close()
+        del qe, ke, ve, oe, le, wse
         # group-wise candidates over one shared, frozen cache (8 candidate chunks, one stream)
         we, G = wl.WORKLOADS["shared_prefix"], 8
         ce = make_cache(we)
@@ -435,23 +458,27 @@ def main() -> int:
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count() or 1
-        n_heads = min(w.heads, 8)  # bounded sample: about 10-20 s of host time
-        orc = RollingCacheOracle(1, n_heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
+        # bounded sample (about 10-20 s of host time): 8 heads of one stream; --cpu-baseline-full: the whole step
+        n_streams, n_heads = (w.batch, w.heads) if args.cpu_baseline_full else (1, min(w.heads, 8))
+        orc = RollingCacheOracle(n_streams, n_heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
                                  w.rope_pairs, w.rope_base)
-        w1 = w.scaled(batch=1, heads=n_heads)
+        w1 = w.scaled(batch=n_streams, heads=n_heads)
         pk, pv = wl.history_frame_pool(w1, 4)
         fk, fv = wl.bf16_bits_to_f32(pk), wl.bf16_bits_to_f32(pv)
         for n in range(min(w.resident_frames, w.capacity_frames)):
-            orc.append_stream(0, fk[n % 4], fv[n % 4], 1)
+            for b in range(n_streams):
+                orc.append_stream(b, fk[wl.pool_index(b, n, 4)], fv[wl.pool_index(b, n, 4)], 1)
         qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in wl.chunk_inputs(w1, with_dout=True))
         t0 = time.perf_counter()
         orc.attn_fwd(qf, kf, vf, w.chunk_frames)
         orc.attn_bwd(qf, kf, vf, dof, w.chunk_frames)
         sec = time.perf_counter() - t0
         fl = flops_fwd(w1) + flops_bwd(w1)
+        what = ("the whole step: every stream and head of the workload" if args.cpu_baseline_full
+                else f"{n_heads} heads of one stream of the workload")
         result["cpu_baseline"] = {"value": round(fl / sec / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-                                  "sample": f"{n_heads} heads of one stream of the workload, forward + backward, "
-                                            f"{fl / 1e9:.1f} GFLOP algorithmic in {sec:.2f} s (fp64 numpy)"}
+                                  "sample": f"{what}, forward + backward, {fl / 1e9:.1f} GFLOP algorithmic in "
+                                            f"{sec:.2f} s (fp64 numpy, {cores} BLAS threads)"}
 
     print(json.dumps(result))
     return 0

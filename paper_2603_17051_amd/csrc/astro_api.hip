@@ -36,6 +36,9 @@ struct astro_kvcache {
     bool valid = false;
   } staged;
   uint64_t epoch = 0;  // bumped by every reset and append: chunk positions may have changed
+  // An append whose launches failed half way leaves ring rows that the tables do not describe:
+  // the handle then refuses work until every stream is reset.
+  bool ring_undefined = false;
   astro_kvcache(const RingGeometry& g, void* k, void* v) : geo(g), tables(g.B, g.C, g.S), k_storage(k), v_storage(v) {}
 };
 
@@ -102,7 +105,7 @@ int check_group(const astro_kvcache* c, int group) {
 
 int check_chunk_call(const astro_kvcache* c, int n_frames, int group) {
   if (!c) return ASTRO_ERR_INVALID_ARG;
-  if (c->geo.host_only) return ASTRO_ERR_BAD_STATE;
+  if (c->geo.host_only || c->ring_undefined) return ASTRO_ERR_BAD_STATE;
   if (n_frames < 1 || n_frames > c->geo.max_chunk) return ASTRO_ERR_INVALID_ARG;
   if (check_group(c, group) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
   if (!c->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
@@ -156,8 +159,13 @@ hipError_t stage_chunk(astro_kvcache* c, const void* q, const void* k_chunk, cha
   StreamInts first, next;
   stream_ints(c, &first, &next, nullptr, group);
   ScatterDst dst{ws + w.q_rot, ws + w.kc_rot, (int64_t)n_frames * c->geo.T, 0};
+  // The bf16 kernels take the queries pre-multiplied by log2(e)/sqrt(D) (applied in fp32 to the
+  // rotated value, before its one rounding to bf16): Q~' K~^T is then directly the exponent of 2,
+  // and the row's reference or log-sum-exp enters as the start value of the MFMA accumulators, so
+  // no multiply-add per score is left in front of the exponential.
+  const float q_scale = c->geo.dtype == ASTRO_BF16 ? 1.4426950408889634f / std::sqrt((float)c->geo.D) : 1.f;
   const hipError_t e = launch_rope_scatter(dev_geom(c, group), c->geo.dtype, q, k_chunk, dst, true, n_frames, first, next,
-                                           (float2*)(ws + w.tab_t), stream);
+                                           (float2*)(ws + w.tab_t), q_scale, stream);
   if (e == hipSuccess) st = astro_kvcache::Staged{q, k_chunk, ws, n_frames, group, c->epoch, true};
   return e;
 }
@@ -245,6 +253,8 @@ int astro_kvcache_destroy(astro_kvcache_t* cache) {
 int astro_kvcache_reset(astro_kvcache_t* cache, int32_t stream, int32_t start_frame) {
   if (!cache) return ASTRO_ERR_INVALID_ARG;
   if (stream < -1 || stream >= cache->geo.B || start_frame < 0) return ASTRO_ERR_INVALID_ARG;
+  if (cache->ring_undefined && stream != -1) return ASTRO_ERR_BAD_STATE;  // only emptying every stream helps
+  cache->ring_undefined = false;
   cache->tables.reset(stream, start_frame);
   ++cache->epoch;
   return ASTRO_OK;
@@ -254,34 +264,44 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
   if (!cache) return ASTRO_ERR_INVALID_ARG;
   const RingGeometry& g = cache->geo;
   if (n_frames < 1 || n_frames > g.max_chunk || n_frames > g.Lw) return ASTRO_ERR_INVALID_ARG;
-  if (!cache->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
+  if (cache->ring_undefined || !cache->tables.can_append(n_frames)) return ASTRO_ERR_BAD_STATE;
   if (!g.host_only) {
     if (!k || !v) return ASTRO_ERR_INVALID_ARG;
+    // Everything is validated; from here on a failing launch leaves ring rows (or sinks) that the
+    // tables do not describe, so it marks the handle instead of pretending nothing happened.
     StreamInts first, next;
     stream_ints(cache, &first, &next, nullptr);
     ScatterDst dst{cache->k_storage, cache->v_storage, (int64_t)g.C * g.T, 1};
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next, nullptr, stream) != hipSuccess)
-      return ASTRO_ERR_HIP;
+    bool ok = true;
     if (g.sinks_move()) {
-      // Window-relative positions.  (1) Sink frames that arrive in this call: keep their keys
-      // un-rotated too.  (2) Streams whose eviction count changes: rotate their sinks again, at
-      // their own index plus the frames evicted once this call's frames are in.  An append holds at
-      // most Lw frames, so a call never does both for one stream.
+      // Window-relative positions, before the ring is touched: sink frames that arrive in this
+      // call keep an un-rotated copy of their keys (written again unchanged if the call is repeated).
       const size_t frame_bytes = (size_t)g.T * g.H * g.D * g.elem_bytes();
+      for (int b = 0; b < g.B && ok; ++b) {
+        const int n0 = cache->tables.next_n(b), n1 = n0 + n_frames;
+        if (n0 >= g.S) continue;
+        const int cnt = n1 < g.S ? n_frames : g.S - n0;
+        const char* src = (const char*)k + (size_t)b * n_frames * frame_bytes;
+        char* dstp = (char*)cache->k_sink_storage + ((size_t)b * g.S + n0) * frame_bytes;
+        ok = hipMemcpyAsync(dstp, src, cnt * frame_bytes, hipMemcpyDeviceToDevice, stream) == hipSuccess;
+      }
+      if (!ok) {  // the ring is untouched: nothing has changed that the tables describe
+        (void)hipGetLastError();
+        return ASTRO_ERR_HIP;
+      }
+    }
+    ok = launch_rope_scatter(dev_geom(cache), g.dtype, k, v, dst, false, n_frames, first, next, nullptr, 1.f, stream) == hipSuccess;
+    if (ok && g.sinks_move()) {
+      // Streams whose eviction count changes: rotate their sinks again, at their own index plus the
+      // frames evicted once this call's frames are in.  An append holds at most Lw frames, so a
+      // call never both receives sinks and evicts for one stream.
       StreamInts first_pos, count;
       bool any = false;
       for (int b = 0; b < ASTRO_MAX_BATCH; ++b) {
         first_pos.v[b] = count.v[b] = 0;
         if (b >= g.B) continue;
         const int n0 = cache->tables.next_n(b), n1 = n0 + n_frames;
-        if (n0 < g.S) {
-          const int cnt = n1 < g.S ? n_frames : g.S - n0;
-          const char* src = (const char*)k + (size_t)b * n_frames * frame_bytes;
-          char* dstp = (char*)cache->k_sink_storage + ((size_t)b * g.S + n0) * frame_bytes;
-          if (hipMemcpyAsync(dstp, src, cnt * frame_bytes, hipMemcpyDeviceToDevice, stream) != hipSuccess)
-            return ASTRO_ERR_HIP;
-        }
         const int ev0 = n0 > g.C ? n0 - g.C : 0, ev1 = n1 > g.C ? n1 - g.C : 0;
         if (ev1 != ev0) {
           first_pos.v[b] = cache->tables.start(b) + ev1;
@@ -289,9 +309,15 @@ int astro_kvcache_append(astro_kvcache_t* cache, const void* k, const void* v, i
           any = true;
         }
       }
-      if (any && launch_rope_sink_rerotate(dev_geom(cache), g.dtype, cache->k_sink_storage, cache->k_storage, first_pos,
-                                           count, stream) != hipSuccess)
-        return ASTRO_ERR_HIP;
+      if (any)
+        ok = launch_rope_sink_rerotate(dev_geom(cache), g.dtype, cache->k_sink_storage, cache->k_storage, first_pos, count,
+                                       stream) == hipSuccess;
+    }
+    if (!ok) {
+      (void)hipGetLastError();
+      cache->ring_undefined = true;
+      cache->staged.valid = false;
+      return ASTRO_ERR_HIP;
     }
   }
   cache->tables.append(n_frames);

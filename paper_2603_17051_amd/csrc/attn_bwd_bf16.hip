@@ -3,7 +3,8 @@
 //   dq    : one workgroup per query tile, walks ALL visible keys (ring + chunk):
 //             Delta[q] = <dO_q, O_q> (taken while the query's dO row is loaded, and
 //             written out for the second kernel),
-//             S^T = K Q~^T, P^T = exp(S^T/sqrt(D) - LSE), dP^T = V dO^T,
+//             S^T = K Q~^T - LSE (Q~ arrives pre-multiplied by log2(e)/sqrt(D) and the accumulators
+//             start from -LSE*log2(e): the product is the exponent of 2), P^T = exp2(S^T), dP^T = V dO^T,
 //             dS^T = P^T o (dP^T - Delta), dQ~^T += K^T dS^T
 //   dkv   : one workgroup per tile of CHUNK keys, walks all query tiles:
 //             S = Q~ K~^T, P, dV^T += dO^T P, dP = dO V^T, dS, dK~^T += Q~^T dS
@@ -45,7 +46,7 @@ struct BwdParams {
   int group;             // candidates per cache stream
   int block_rows;        // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;
-  float scale_log2e, scale;
+  float scale;
   StreamInts hist_rows;
 };
 
@@ -57,18 +58,16 @@ struct DqWave {
   static constexpr int KS = D / 32;  // k-steps of a contraction over D
   static constexpr int DT = D / 16;  // 16-row tiles of dQ~^T
   bf16x8 qreg[2][KS], doreg[2][KS];  // B operands: Q~ and dO rows of this lane's two queries
-  float neg_lse2[2];   // -LSE*log2(e) of the two queries
+  f32x4 neg_lse2[2];   // -LSE*log2(e) of the two queries, four copies: the accumulators of S start from it
   // -Delta of the two queries, four copies each: the accumulators of dP^T start from them, so
   // the product comes out as dP^T - Delta
   f32x4 neg_delta[2];
   f32x4 dq[DT][2];
   OperandAddr16<D> addr;
   int g;
-  float scale_log2e;
 
-  __device__ __forceinline__ void init(int lane, float sl2e) {
+  __device__ __forceinline__ void init(int lane) {
     g = lane >> 4;
-    scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -77,16 +76,15 @@ struct DqWave {
   }
 
   // ---- the pieces of one 32-key block kb of a tile -------------------------------------
-  // S^T = K Q~^T: 16 MFMAs, each pair behind the read of its K fragment
+  // S^T - LSE*log2(e) = K Q~^T - LSE*log2(e): 16 MFMAs, each pair behind the read of its K fragment
   __device__ __forceinline__ void s_product(const char* ks, int kb, f32x4 (&s)[2][2]) const {
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st = 0; st < KS; ++st)
 #pragma unroll
       for (int kh = 0; kh < 2; ++kh) {
         const bf16x8 a = read_rows16<D>(ks, addr.row[st], 32 * kb + 16 * kh);
 #pragma unroll
-        for (int qs = 0; qs < 2; ++qs) s[kh][qs] = mfma16(a, qreg[qs][st], st == 0 ? zero : s[kh][qs]);
+        for (int qs = 0; qs < 2; ++qs) s[kh][qs] = mfma16(a, qreg[qs][st], st == 0 ? neg_lse2[qs] : s[kh][qs]);
       }
   }
   // keys of the block that do not count for a query: score replaced so that P and dS are exactly 0
@@ -98,14 +96,14 @@ struct DqWave {
 #pragma unroll
         for (int r = 0; r < 4; ++r) s[kh][qs][r] = 32 * kb + 16 * kh + 4 * g + r >= live[qs] ? kNegBig : s[kh][qs][r];
   }
-  // P^T = exp2(S^T * scale*log2(e) - LSE*log2(e)), in place: 32 vector-ALU instructions
+  // P^T = exp2(S^T - LSE*log2(e)), in place: 16 exponentials
   __device__ __forceinline__ void probabilities(f32x4 (&s)[2][2]) const {
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs)
 #pragma unroll
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) s[kh][qs][r] = fast_exp2(fmaf(s[kh][qs][r], scale_log2e, neg_lse2[qs]));
+        for (int r = 0; r < 4; ++r) s[kh][qs][r] = fast_exp2(s[kh][qs][r]);
   }
   // dP^T - Delta = V dO^T - Delta: 16 MFMAs
   __device__ __forceinline__ void dp_product(const char* vs, int kb, f32x4 (&dp)[2][2]) const {
@@ -207,7 +205,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
   const int ntiles = hist_tiles + (vis_wg + KT - 1) / KT;
 
   Wave w;
-  w.init(lane, p.scale_log2e);
+  w.init(lane);
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     const int q = q0 + 16 * qs;
@@ -236,7 +234,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_bwd_dq_kernel(BwdParams
     dsum += __shfl_xor(dsum, 32);
     // a dead query row gets P = exp2(0 - big) = 0 everywhere
     const float nl = live ? -p.lse[bh * p.Nq + q] * kLog2e : -1.0e30f;
-    w.neg_lse2[qs] = nl;
+    w.neg_lse2[qs] = f32x4{nl, nl, nl, nl};
     w.neg_delta[qs] = f32x4{-dsum, -dsum, -dsum, -dsum};
     // the row terms of the query, for the dK/dV kernel (negative there too)
     if (live && g == 0) {
@@ -329,6 +327,20 @@ struct DkvLds {
   static_assert(kTotal <= 160 * 1024, "one workgroup per CU must fit the LDS");
 };
 
+// Scheduling pattern for a product of kSteps operand fragments (kReads LDS reads and two MFMAs
+// each) placed next to independent vector-ALU work: fragment reads run one step ahead of their
+// MFMAs, and each pair of MFMAs is followed by a share of the vector-ALU instructions.
+template <int kSteps, int kReads>
+__device__ __forceinline__ void interleave() {
+  __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReads, 0);  // the first two fragments
+#pragma unroll
+  for (int i = 0; i < kSteps; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // two MFMAs
+    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);  // vector-ALU work of the other block
+    if (i + 2 < kSteps) __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);  // the fragment after next
+  }
+}
+
 // 16x16x32 MFMAs: a wave's 32 keys are two sub-blocks of 16 (ks); lane (i = lane % 16,
 // g = lane / 16) holds, for keys 16*ks + i, the accumulator rows 4g .. 4g+3 of every 16-row tile.
 // Tile rows below first[ks] (per lane; first_max, wave-uniform, = the largest over the wave) are
@@ -341,11 +353,9 @@ struct ValueWave {
   f32x4 dv[DT][2];
   OperandAddr16<D> addr;
   int g;
-  float scale_log2e;
 
-  __device__ __forceinline__ void init(int lane, float sl2e) {
+  __device__ __forceinline__ void init(int lane) {
     g = lane >> 4;
-    scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -353,53 +363,80 @@ struct ValueWave {
       for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // qs / dos = Q~ and dO tiles, lse_t = -LSE*log2(e) of the tile's rows, probs = this wave's part of a P slot
-  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs,
-                                       const int (&first)[2], int first_max) {
+  // ---- the three phases of one block of 32 queries qb of a tile --------------------------
+  // S[q][key] - LSE[q]*log2(e), the exponent of 2 (Q~ is pre-multiplied, the accumulators start from
+  // the rows' terms): rows = 32 queries in two halves of 16 (qh), column = the lane's key ks
+  __device__ __forceinline__ void s_product(const char* qs, int qb, const f32x4 (&l4)[2], f32x4 (&s)[2][2]) const {
 #pragma unroll
-    for (int qb = 0; qb < QT / 32; ++qb) {
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-      // S[q][key]: rows = 32 queries of the tile in two halves of 16 (qh), column = the lane's key
-      // ks; the row terms are requested ahead of the product whose result they meet
-      f32x4 s[2][2], l4[2];
+    for (int st = 0; st < KS; ++st)
 #pragma unroll
-      for (int qh = 0; qh < 2; ++qh) l4[qh] = *reinterpret_cast<const f32x4*>(lse_t + 32 * qb + 16 * qh + 4 * g);
+      for (int qh = 0; qh < 2; ++qh) {
+        const bf16x8 a = read_rows16<D>(qs, addr.row[st], 32 * qb + 16 * qh);
 #pragma unroll
-      for (int st = 0; st < KS; ++st)
-#pragma unroll
-        for (int qh = 0; qh < 2; ++qh) {
-          const bf16x8 a = read_rows16<D>(qs, addr.row[st], 32 * qb + 16 * qh);
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks) s[qh][ks] = mfma16(a, kreg[ks][st], st == 0 ? zero : s[qh][ks]);
-        }
-      if (first_max > 32 * qb) {
-#pragma unroll
-        for (int qh = 0; qh < 2; ++qh)
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) s[qh][ks][r] = 32 * qb + 16 * qh + 4 * g + r < first[ks] ? kNegBig : s[qh][ks][r];
+        for (int ks = 0; ks < 2; ++ks) s[qh][ks] = mfma16(a, kreg[ks][st], st == 0 ? l4[qh] : s[qh][ks]);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      // P as the B operand of the next product: k-slots 8g .. 8g+3 <- queries 4g .., 8g+4 .. <- queries 16 + 4g ..
-      bf16x8 pb[2];
+  }
+  // queries of an earlier causal block than the lane's key do not see it: P = 0
+  __device__ __forceinline__ void mask(int qb, const int (&first)[2], f32x4 (&s)[2][2]) const {
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int qh = 0; qh < 2; ++qh)
+        for (int r = 0; r < 4; ++r) s[qh][ks][r] = 32 * qb + 16 * qh + 4 * g + r < first[ks] ? kNegBig : s[qh][ks][r];
+  }
+  // P as the B operand of the next product (k-slots 8g .. 8g+3 <- queries 4g .., 8g+4 .. <- queries
+  // 16 + 4g ..), also handed to the key wave through LDS
+  __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][2], int qb, char* probs, bf16x8 (&pb)[2]) const {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) pb[ks][4 * qh + r] = (__bf16)fast_exp2(fmaf(s[qh][ks][r], scale_log2e, l4[qh][r]));
-      *reinterpret_cast<bf16x8*>(probs + (2 * qb) * 1024) = pb[0];
-      *reinterpret_cast<bf16x8*>(probs + (2 * qb + 1) * 1024) = pb[1];
-      __builtin_amdgcn_sched_barrier(0);
-      // dV^T[d][key] += dO^T[d][q] P[q][key]
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const bf16x8 a = read_cols16<D>(dos, addr.tr[dt], 32 * qb);
+      for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = mfma16(a, pb[ks], dv[dt][ks]);
-      }
+        for (int r = 0; r < 4; ++r) pb[ks][4 * qh + r] = (__bf16)fast_exp2(s[qh][ks][r]);
+    *reinterpret_cast<bf16x8*>(probs + (2 * qb) * 1024) = pb[0];
+    *reinterpret_cast<bf16x8*>(probs + (2 * qb + 1) * 1024) = pb[1];
+  }
+  // dV^T[d][key] += dO^T[d][q] P[q][key]
+  __device__ __forceinline__ void dv_product(const char* dos, int qb, const bf16x8 (&pb)[2]) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 a = read_cols16<D>(dos, addr.tr[dt], 32 * qb);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) dv[dt][ks] = mfma16(a, pb[ks], dv[dt][ks]);
     }
+  }
+
+  // One tile of 64 queries = two blocks.  A wave's own MFMAs and vector-ALU work overlap only when
+  // independent instructions of both kinds are next to each other, so the blocks are software
+  // pipelined: the exponentials of block 0 sit between the MFMAs of S(1), those of block 1 between
+  // the MFMAs of dV(0).  (Phase by phase, as it was before, a period took about twice the time of
+  // its MFMAs.)
+  // qs / dos = Q~ and dO tiles, lse_t = -LSE*log2(e) of the tile's rows, probs = this wave's part of a P slot
+  __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* lse_t, char* probs,
+                                       const int (&first)[2], int first_max) {
+    static_assert(QT == 64, "two blocks per tile");
+    f32x4 s0[2][2], s1[2][2], l0[2], l1[2];
+    bf16x8 p0[2], p1[2];
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+      l0[qh] = *reinterpret_cast<const f32x4*>(lse_t + 16 * qh + 4 * g);
+      l1[qh] = *reinterpret_cast<const f32x4*>(lse_t + 32 + 16 * qh + 4 * g);
+    }
+    s_product(qs, 0, l0, s0);
+    if (first_max > 0) mask(0, first, s0);
+    __builtin_amdgcn_sched_barrier(0);
+    s_product(qs, 1, l1, s1);
+    probabilities(s0, 0, probs, p0);
+    interleave<2 * KS, 1>();
+    __builtin_amdgcn_sched_barrier(0);
+    if (first_max > 32) mask(1, first, s1);
+    __builtin_amdgcn_sched_barrier(0);
+    dv_product(dos, 0, p0);
+    probabilities(s1, 1, probs, p1);
+    interleave<DT, 2>();
+    __builtin_amdgcn_sched_barrier(0);
+    dv_product(dos, 1, p1);
   }
 };
 
@@ -421,43 +458,64 @@ struct KeyWave {
       for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // dP[q][key] - Delta[q] = <dO_q, V_key> - Delta[q]: the accumulators start from the rows' terms
+  __device__ __forceinline__ void dp_product(const char* dos, int qb, const f32x4 (&d4)[2], f32x4 (&dp)[2][2]) const {
+#pragma unroll
+    for (int st = 0; st < KS; ++st)
+#pragma unroll
+      for (int qh = 0; qh < 2; ++qh) {
+        const bf16x8 a = read_rows16<D>(dos, addr.row[st], 32 * qb + 16 * qh);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) dp[qh][ks] = mfma16(a, vreg[ks][st], st == 0 ? d4[qh] : dp[qh][ks]);
+      }
+  }
+  // dS = P o (dP - Delta) as the B operand of the last product
+  __device__ __forceinline__ void ds_operand(const bf16x8 (&pb)[2], const f32x4 (&dp)[2][2], bf16x8 (&dsb)[2]) const {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dsb[ks][4 * qh + r] = (__bf16)((float)pb[ks][4 * qh + r] * dp[qh][ks][r]);
+  }
+  // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
+  __device__ __forceinline__ void dk_product(const char* qs, int qb, const bf16x8 (&dsb)[2]) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 a = read_cols16<D>(qs, addr.tr[dt], 32 * qb);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = mfma16(a, dsb[ks], dk[dt][ks]);
+    }
+  }
+
+  // One tile of 64 queries, software pipelined like the value wave's: dS of block 0 is formed
+  // between the MFMAs of dP(1), dS of block 1 between those of dK(0).
   // qs / dos = Q~ and dO tiles, delta_t = -Delta of the tile's rows, probs = the partner's P of this tile
   __device__ __forceinline__ void tile(const char* qs, const char* dos, const float* delta_t, const char* probs) {
+    static_assert(QT == 64, "two blocks per tile");
+    f32x4 dp0[2][2], dp1[2][2], d0[2], d1[2];
+    bf16x8 p0[2], p1[2], ds0[2], ds1[2];
 #pragma unroll
-    for (int qb = 0; qb < QT / 32; ++qb) {
-      f32x4 dp[2][2], d4[2];
-      bf16x8 pb[2];
-#pragma unroll
-      for (int qh = 0; qh < 2; ++qh) d4[qh] = *reinterpret_cast<const f32x4*>(delta_t + 32 * qb + 16 * qh + 4 * g);
-      pb[0] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb) * 1024);
-      pb[1] = *reinterpret_cast<const bf16x8*>(probs + (2 * qb + 1) * 1024);
-      // dP[q][key] - Delta[q] = <dO_q, V_key> - Delta[q]: the accumulators start from the rows' terms
-#pragma unroll
-      for (int st = 0; st < KS; ++st)
-#pragma unroll
-        for (int qh = 0; qh < 2; ++qh) {
-          const bf16x8 a = read_rows16<D>(dos, addr.row[st], 32 * qb + 16 * qh);
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks) dp[qh][ks] = mfma16(a, vreg[ks][st], st == 0 ? d4[qh] : dp[qh][ks]);
-        }
-      __builtin_amdgcn_sched_barrier(0);
-      bf16x8 dsb[2];
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int qh = 0; qh < 2; ++qh)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            dsb[ks][4 * qh + r] = (__bf16)((float)pb[ks][4 * qh + r] * dp[qh][ks][r]);
-      __builtin_amdgcn_sched_barrier(0);
-      // dK~^T[d][key] += Q~^T[d][q] dS[q][key]
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const bf16x8 a = read_cols16<D>(qs, addr.tr[dt], 32 * qb);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) dk[dt][ks] = mfma16(a, dsb[ks], dk[dt][ks]);
-      }
+    for (int qh = 0; qh < 2; ++qh) {
+      d0[qh] = *reinterpret_cast<const f32x4*>(delta_t + 16 * qh + 4 * g);
+      d1[qh] = *reinterpret_cast<const f32x4*>(delta_t + 32 + 16 * qh + 4 * g);
     }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      p0[ks] = *reinterpret_cast<const bf16x8*>(probs + ks * 1024);
+      p1[ks] = *reinterpret_cast<const bf16x8*>(probs + (2 + ks) * 1024);
+    }
+    dp_product(dos, 0, d0, dp0);
+    __builtin_amdgcn_sched_barrier(0);
+    dp_product(dos, 1, d1, dp1);
+    ds_operand(p0, dp0, ds0);
+    interleave<2 * KS, 1>();
+    __builtin_amdgcn_sched_barrier(0);
+    dk_product(qs, 0, ds0);
+    ds_operand(p1, dp1, ds1);
+    interleave<DT, 2>();
+    __builtin_amdgcn_sched_barrier(0);
+    dk_product(qs, 1, ds1);
   }
 };
 
@@ -488,10 +546,7 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
   const int t_begin = first_query_row_seeing(item.tile * 128, block_rows) / QT;
 
   Wave w;
-  if constexpr (kKey)
-    w.init(lane);
-  else
-    w.init(lane, p.scale_log2e);
+  w.init(lane);
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     // B operand of the role's first product: V row (key wave) or K~ row (value wave) of the lane's key ks
@@ -588,7 +643,7 @@ __device__ __forceinline__ void dkv_wave(const BwdParams& p, const WorkItem& ite
     for (int dt = 0; dt < D / 16; ++dt) {
       f32x4 x;
       if constexpr (kKey) {
-        x = w.dk[dt][ks] * p.scale;
+        x = w.dk[dt][ks] * kLn2;  // dK~ = dS^T Q~ / sqrt(D), and the staged Q~ carries log2(e)/sqrt(D)
         if (rope) x = unrotate_quad(p.rot, tt, 4 * dt + g, x);
       } else {
         x = w.dv[dt][ks];
@@ -638,7 +693,6 @@ BwdParams make_params(const DevGeom& g, const AttnOperands& op, const void* out,
   p.Nq = op.Nq;
   p.cache_rows = (int64_t)g.C * g.T;
   p.scale = 1.0f / sqrtf((float)D);
-  p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   p.group = op.group;
   p.block_rows = op.block_rows;

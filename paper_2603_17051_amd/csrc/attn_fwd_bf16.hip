@@ -5,7 +5,8 @@
 // 32; K and V tiles are streamed into a ring of LDS stages by direct-to-LDS loads issued
 // two tiles ahead, one barrier per tile.  Everything is computed transposed so that
 // every lane owns ONE query:
-//   S^T[key][q] = K * Q~^T      (A = K tile from LDS, B = Q~ held in registers)
+//   S^T[key][q] = K * Q~^T      (A = K tile from LDS, B = Q~ held in registers; Q~ arrives
+//                                pre-multiplied by log2(e)/sqrt(D), so S^T is the exponent of 2)
 //   O^T[d][q]  += V^T * P^T     (A = V tile through the transposing LDS read,
 //                                B = P^T taken straight from the S^T accumulators)
 // so the row maximum / sum of the softmax are in-lane reductions plus one exchange with
@@ -52,7 +53,6 @@ struct FwdParams {
   int H, Nq, BH, q_tiles, group;  // BH = candidates * heads; group = candidates per cache stream
   int block_rows;                 // causal block inside the chunk in token rows, 0 = none
   int64_t cache_rows;  // C*T
-  float scale_log2e, scale;
   StreamInts hist_rows;
 };
 
@@ -68,14 +68,12 @@ struct FwdWave {
 
   bf16x8 qreg[2][KS];
   f32x4 o[DT][2];
-  float mc[2], l_run[2];  // softmax reference in log2 units (scale*log2(e) * dot), per-lane partial row sum
+  float mc[2], l_run[2];  // softmax reference in log2 units (the units of the scores), per-lane partial row sum
   OperandAddr16<D> addr;
   int g;
-  float scale_log2e;
 
-  __device__ __forceinline__ void init(int lane, float sl2e) {
+  __device__ __forceinline__ void init(int lane) {
     g = lane >> 4;
-    scale_log2e = sl2e;
     addr.init(lane);
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
@@ -88,7 +86,7 @@ struct FwdWave {
       for (int qs = 0; qs < 2; ++qs) o[dt][qs] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // p = exp2(s * scale*log2(e) - mc) rounded to bf16, packed as the B operands of the PV
+  // p = exp2(s - mc) rounded to bf16, packed as the B operands of the PV
   // product (k-slots 8g .. 8g+3 <- keys 4g .., 8g+4 .. <- keys 16 + 4g ..); sum = this lane's
   // part of the row sums, taken over the rounded values.
   __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][2], bf16x8 (&pb)[2], float (&sum)[2]) const {
@@ -99,8 +97,7 @@ struct FwdWave {
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
         for (int r = 0; r < 4; r += 2) {
-          const f32x2 e = {fast_exp2(fmaf(s[kh][qs][r], scale_log2e, -mc[qs])),
-                           fast_exp2(fmaf(s[kh][qs][r + 1], scale_log2e, -mc[qs]))};
+          const f32x2 e = {fast_exp2(s[kh][qs][r] - mc[qs]), fast_exp2(s[kh][qs][r + 1] - mc[qs])};
           const bf16x2 pk = __builtin_convertvector(e, bf16x2);
           sum[qs] = add_pair(pk, sum[qs]);
           pb[qs][4 * kh + r] = pk[0];
@@ -191,7 +188,9 @@ struct FwdWave {
         mx = fmaxf(mx, fmaxf(fmaxf(s[1][qs][0], s[1][qs][1]), fmaxf(s[1][qs][2], s[1][qs][3])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));  // over the four lanes that share the query
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mc_new = fmaxf(mc[qs], mx * scale_log2e);
+        // never below -1e28: a query that has seen nothing but masked keys so far (scores of
+        // -1e30) keeps probabilities of exactly 0 instead of exp2(rounding error of 1e29)
+        const float mc_new = fmaxf(fmaxf(mc[qs], mx), -1.0e28f);
         const float alpha = fast_exp2(mc[qs] - mc_new);
         l_run[qs] *= alpha;
         // whole-tuple products: the compiler then updates the accumulators where they are
@@ -272,7 +271,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
   const int64_t bh = (int64_t)b * p.H + h;
 
   Wave w;
-  w.init(lane, p.scale_log2e);
+  w.init(lane);
   // Q~ as the B operand: lane (i, g) holds Q~[q][32*st + 8g .. +7] of its two queries
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
@@ -385,13 +384,18 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
     out = p.out_part + (int64_t)split * ((int64_t)p.BH * p.Nq * D);
     lse = p.lse_part + (int64_t)split * ((int64_t)p.BH * p.Nq);
   }
+  // A key range in which a query sees nothing (no tiles at all: a split of a workgroup that sees
+  // few keys under the causal mask; or only keys of later causal blocks: row sum 0) reports zero
+  // output and a log-sum-exp of -1e30, which is weight 0 in the merge.  Every query sees its own
+  // block, so some range of it is real.
 #pragma unroll
   for (int qs = 0; qs < 2; ++qs) {
     // the query's row sum: over the four lanes that share it
     float l_tot = w.l_run[qs];
     l_tot += __shfl_xor(l_tot, 16);
     l_tot += __shfl_xor(l_tot, 32);
-    const float inv = 1.f / l_tot;
+    const bool nothing = !(l_tot > 0.f);
+    const float inv = nothing ? 0.f : 1.f / l_tot;
     const int q = q0 + 16 * qs;
     if (q < p.Nq) {
       __bf16* orow = out + (((int64_t)b * p.Nq + q) * p.H + h) * D;
@@ -402,7 +406,7 @@ __global__ void __launch_bounds__(kWaves * 64, OCC) attn_fwd_bf16_kernel(FwdPara
         for (int c = 0; c < 4; ++c) x[c] = (__bf16)(w.o[dt][qs][c] * inv);
         *reinterpret_cast<bf16x4*>(orow + 16 * dt + 4 * g) = x;
       }
-      if (g == 0) lse[bh * p.Nq + q] = w.mc[qs] * kLn2 + __logf(l_tot);
+      if (g == 0) lse[bh * p.Nq + q] = nothing ? kNegBig : w.mc[qs] * kLn2 + __logf(l_tot);
     }
   }
 }
@@ -453,8 +457,6 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.H = g.H;
   p.Nq = op.Nq;
   p.cache_rows = (int64_t)g.C * g.T;
-  p.scale = 1.0f / sqrtf((float)D);
-  p.scale_log2e = p.scale * kLog2e;
   p.hist_rows = op.hist_rows;
   p.group = op.group;
   p.block_rows = op.block_rows;
@@ -462,7 +464,7 @@ hipError_t launch(const DevGeom& g, const AttnOperands& op, void* out, float* ls
   p.BH = g.B * g.H;
   p.q_tiles = (op.Nq + qtile - 1) / qtile;
   // a launch that would leave the chip under two rounds of workgroups is split over the keys
-  p.splits = kCausal ? 1 : bf16_fwd_splits(g, op, parts != nullptr);
+  p.splits = bf16_fwd_splits(g, op, parts != nullptr);
   p.out_part = (__bf16*)parts;
   p.lse_part = (float*)((char*)parts + (size_t)p.splits * p.BH * op.Nq * D * 2);
   dim3 grid(work_grid_size(p.q_tiles, p.BH * p.splits));
@@ -495,12 +497,16 @@ size_t bf16_fwd_split_bytes(const DevGeom& g, int Nq) {
 }
 
 int bf16_fwd_splits(const DevGeom& g, const AttnOperands& op, bool have_parts) {
-  if (!have_parts || op.block_rows > 0) return 1;
+  if (!have_parts) return 1;
   const int items = fwd_work_items(g, op.Nq), places = kFwdWorkgroupsPerCu * g.n_cus;
   if (items >= 2 * places) return 1;
   int min_hist = INT32_MAX;
   for (int b = 0; b < g.B / op.group; ++b) min_hist = op.hist_rows.v[b] < min_hist ? op.hist_rows.v[b] : min_hist;
-  const int tiles = (min_hist + KT - 1) / KT + (op.Nq + KT - 1) / KT;
+  // key tiles of the workgroup that sees the fewest: under causal blocks that is the first query
+  // tile, which sees one block of the chunk (a range may still come out empty or unseen for some
+  // queries: both report weight 0 to the merge)
+  const int chunk_rows = op.block_rows > 0 && op.block_rows < op.Nq ? op.block_rows : op.Nq;
+  const int tiles = (min_hist + KT - 1) / KT + (chunk_rows + KT - 1) / KT;
   int s = (2 * places + items - 1) / items;
   if (s > kMaxFwdSplits) s = kMaxFwdSplits;
   if (s > tiles / kMinTilesPerSplit) s = tiles / kMinTilesPerSplit;

@@ -53,10 +53,11 @@ struct ScatterDst {
 // first frame, next_n.v[b] = its stream-local number.
 // tab_t_out (may be null): [B][n_frames][n_t] (cos, sin) of the temporal pairs at each chunk frame's
 // position, exactly the values this launch rotates with, for the kernels that rotate gradients back.
+// a_scale: factor applied to the rotated `a` before it is rounded for storage (1 = none).
 hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in,
                                ScatterDst dst, bool rotate_b, int n_frames,
                                const StreamInts& first_frame, const StreamInts& next_n,
-                               float2* tab_t_out, hipStream_t stream);
+                               float2* tab_t_out, float a_scale, hipStream_t stream);
 
 // Inverse rotation of fp32 gradients: src head-major [B][H][n_frames*T][D] (rotated frame)
 // -> dst [B, n_frames*T, H, D] (un-rotated frame).
@@ -84,7 +85,7 @@ hipError_t launch_rope_sink_rerotate(const DevGeom& g, int dtype, const void* si
 // cache stream (candidate c = b*group + g, DevGeom::B counts candidates); all candidates of
 // stream b see that stream's ring rows and only their own chunk rows.
 struct AttnOperands {
-  const void* q_rot;    // [B][H][Nq][D] rotated queries (workspace)
+  const void* q_rot;    // [B][H][Nq][D] rotated queries (workspace); bf16 path: times log2(e)/sqrt(D)
   const void* kc_rot;   // [B][H][Nq][D] rotated chunk keys (workspace)
   const void* v_chunk;  // [B, Nq, H, D] caller's chunk values
   const void* k_cache;  // [B][H][C*T][D]

@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const
                                                                 const Elem* __restrict__ b_in, Elem* __restrict__ a_out,
                                                                 Elem* __restrict__ b_out, int64_t rows_per_head, int ring,
                                                                 int n_frames, StreamInts first_frame, StreamInts next_n,
-                                                                float2* __restrict__ tab_t_out) {
+                                                                float2* __restrict__ tab_t_out, float a_scale) {
   constexpr int EPC = 16 / sizeof(Elem);  // elements per 16-byte chunk
   __shared__ float2 tab[kMaxBlockPairs];
   const int fi = blockIdx.x / g.gh, row = blockIdx.x % g.gh;
@@ -91,14 +91,18 @@ __global__ void __launch_bounds__(kThreads) rope_scatter_kernel(DevGeom g, const
           for (int v = 0; v < 4; ++v) {
             const float2 cs = pair_cs(tab, g, w, c * 4 + v);
             const float a0 = (float)xa[u][2 * v], a1 = (float)xa[u][2 * v + 1];
-            xa[u][2 * v] = (__bf16)(a0 * cs.x - a1 * cs.y);
-            xa[u][2 * v + 1] = (__bf16)(a0 * cs.y + a1 * cs.x);
+            xa[u][2 * v] = (__bf16)((a0 * cs.x - a1 * cs.y) * a_scale);
+            xa[u][2 * v + 1] = (__bf16)((a0 * cs.y + a1 * cs.x) * a_scale);
             if (kRotateB) {
               const float b0 = (float)xb[u][2 * v], b1 = (float)xb[u][2 * v + 1];
               xb[u][2 * v] = (__bf16)(b0 * cs.x - b1 * cs.y);
               xb[u][2 * v + 1] = (__bf16)(b0 * cs.y + b1 * cs.x);
             }
           }
+        }
+        if (!rope && a_scale != 1.f) {
+#pragma unroll
+          for (int v = 0; v < 8; ++v) xa[u][v] = (__bf16)((float)xa[u][v] * a_scale);
         }
         if constexpr (kRotateB) {  // staged Q~, K~: read again at once by the attention launch
           *reinterpret_cast<bf16x8*>(a_out + out_off) = xa[u];
@@ -226,7 +230,7 @@ __global__ void __launch_bounds__(kThreads) rope_sink_rerotate_kernel(DevGeom g,
 
 hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, const void* b_in, ScatterDst dst,
                                bool rotate_b, int n_frames, const StreamInts& first_frame, const StreamInts& next_n,
-                               float2* tab_t_out, hipStream_t stream) {
+                               float2* tab_t_out, float a_scale, hipStream_t stream) {
   dim3 grid(n_frames * g.gh, g.H, g.B), block(kThreads);
   ProfileScope prof(dst.ring ? "kv_append_rope" : "chunk_rope_stage", stream);
   if (dtype == ASTRO_BF16) {
@@ -234,19 +238,19 @@ hipError_t launch_rope_scatter(const DevGeom& g, int dtype, const void* a_in, co
     auto b = static_cast<const __bf16*>(b_in);
     if (rotate_b)
       rope_scatter_kernel<__bf16, true><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
-                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out, a_scale);
     else
       rope_scatter_kernel<__bf16, false><<<grid, block, 0, stream>>>(g, a, b, (__bf16*)dst.a, (__bf16*)dst.b,
-                                                                    dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
+                                                                    dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out, a_scale);
   } else {
     auto a = static_cast<const float*>(a_in);
     auto b = static_cast<const float*>(b_in);
     if (rotate_b)
       rope_scatter_kernel<float, true><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
-                                                                  dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
+                                                                  dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out, a_scale);
     else
       rope_scatter_kernel<float, false><<<grid, block, 0, stream>>>(g, a, b, (float*)dst.a, (float*)dst.b,
-                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out);
+                                                                   dst.rows_per_head, dst.ring, n_frames, first_frame, next_n, tab_t_out, a_scale);
   }
   return hipGetLastError();
 }

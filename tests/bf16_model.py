@@ -6,7 +6,8 @@ products", which is what the normalised error gates of the GPU parity tests are 
 (gate <= 2 x the model's error on the same kind of input).
 
 Roundings modelled (everything else in fp64):
-  * rotated queries, rotated chunk keys and rotated cached keys are stored as bf16;
+  * rotated queries (multiplied by log2(e)/sqrt(D) before the rounding, so that their products with
+    the keys are exponents of 2), rotated chunk keys and rotated cached keys are stored as bf16;
   * the probabilities that enter the P V product are bf16 (and the row sum is taken over the
     rounded values); the output is stored as bf16;
   * backward: S is recomputed from the bf16 rotated operands, Delta = <dO, O> uses the bf16 output,
@@ -26,23 +27,24 @@ def model_fwd_bwd(orc: RollingCacheOracle, q, k_chunk, v_chunk, dout, n_frames: 
     same un-rotated fp64 arrays the oracle gets.  Whole-chunk block (no causal blocks)."""
     D = orc.D
     scale = 1.0 / np.sqrt(np.float64(D))
+    log2e, ln2 = 1.0 / np.log(2.0), np.log(2.0)
     phi = orc._chunk_phi(b, n_frames)
-    qt = round_to_bf16(rope_rotate(np.asarray(q[b, :, h:h + 1, :], dtype=np.float64), phi)[:, 0])
+    qt = round_to_bf16(scale * log2e * rope_rotate(np.asarray(q[b, :, h:h + 1, :], dtype=np.float64), phi)[:, 0])
     kc = round_to_bf16(rope_rotate(np.asarray(k_chunk[b, :, h:h + 1, :], dtype=np.float64), phi)[:, 0])
     kh, vh = orc._context(b, h)
     kt = np.concatenate([round_to_bf16(kh), kc], 0)
     nh = kh.shape[0]
     vv = np.concatenate([vh, np.asarray(v_chunk[b, :, h, :], dtype=np.float64)], 0)
     do = np.asarray(dout[b, :, h, :], dtype=np.float64)
-    # forward
-    s = (qt @ kt.T) * scale
-    m = s.max(axis=1, keepdims=True)
-    p_b = round_to_bf16(np.exp(s - m))
+    # forward, in exponents of 2
+    s2 = qt @ kt.T
+    m2 = s2.max(axis=1, keepdims=True)
+    p_b = round_to_bf16(np.exp2(s2 - m2))
     z = p_b.sum(axis=1, keepdims=True)
     out = round_to_bf16((p_b @ vv) / z)
-    lse = (m + np.log(z))[:, 0]
+    lse = ((m2 + np.log2(z)) * ln2)[:, 0]
     # backward
-    p = np.exp(s - lse[:, None])
+    p = np.exp2(s2 - lse[:, None] * log2e)
     delta = (do * out).sum(axis=1, keepdims=True)
     dp = do @ vv.T
     ds_b = round_to_bf16(p * (dp - delta))
@@ -50,7 +52,7 @@ def model_fwd_bwd(orc: RollingCacheOracle, q, k_chunk, v_chunk, dout, n_frames: 
     # the key-side kernel multiplies the bf16 probabilities it also uses for P^T dO
     pk_b = round_to_bf16(p[:, nh:])
     dsk_b = round_to_bf16(pk_b * (dp[:, nh:] - delta))
-    dkt = scale * (dsk_b.T @ qt)
+    dkt = ln2 * (dsk_b.T @ qt)   # the stored queries carry log2(e)/sqrt(D)
     dv = pk_b.T @ do
     dq = rope_rotate(dqt[:, None, :], -phi)[:, 0]
     dk = rope_rotate(dkt[:, None, :], -phi)[:, 0]

@@ -64,18 +64,23 @@ def assert_bf16_close(got, ref, what: str, report=None):
 
 
 def assert_within_model(got, ref, model, what: str, report=None):
-    """For inputs outside the N(0,1) contract: the error against the fp64 reference may be
-    MODEL_FACTOR times the error of the bf16 rounding model on the same inputs (max and rms), plus
-    a floor for what the model leaves out (fp32 accumulation of the products, fp32 exp2)."""
+    """For inputs outside the N(0,1) contract (the absolute bound does not apply): the error
+    against the fp64 reference must stay within the normalised gates, or, where the bf16 rounding
+    model on the SAME inputs says those cannot hold (a rounded dS meeting keys with a large common
+    offset, rotated keys at large logits), within MODEL_FACTOR times the model's error; plus a floor
+    for what the model leaves out (fp32 accumulation of the products, fp32 exp2).  One realisation
+    of the model's largest error is itself noisy, hence the 'or'."""
     assert np.isfinite(got).all(), f"{what}: non-finite values in the GPU result"
     e, em = got - ref, model - ref
     floor = 2e-5 * max(1.0, float(np.abs(ref).max()))
     mx, mx_m = float(np.abs(e).max()), float(np.abs(em).max())
     rms, rms_m = float(np.sqrt(np.mean(e ** 2))), float(np.sqrt(np.mean(em ** 2)))
+    mx_gate = max(MODEL_FACTOR * mx_m, BF16_MAX_OVER_MAX * float(np.abs(ref).max())) + floor
+    rms_gate = max(MODEL_FACTOR * rms_m, BF16_RMS_OVER_RMS * float(np.sqrt(np.mean(ref ** 2)))) + floor
     if report is not None:
-        report.append(f"{what}: max_abs={mx:.3e} (model {mx_m:.3e}) rms={rms:.3e} (model {rms_m:.3e})")
-    assert mx <= MODEL_FACTOR * mx_m + floor, f"{what}: max abs err {mx}, rounding model {mx_m}"
-    assert rms <= MODEL_FACTOR * rms_m + floor, f"{what}: rms err {rms}, rounding model {rms_m}"
+        report.append(f"{what}: max_abs={mx:.3e} (model {mx_m:.3e}, gate {mx_gate:.3e}) rms={rms:.3e} (model {rms_m:.3e}, gate {rms_gate:.3e})")
+    assert mx <= mx_gate, f"{what}: max abs err {mx}, rounding model {mx_m}, gate {mx_gate}"
+    assert rms <= rms_gate, f"{what}: rms err {rms}, rounding model {rms_m}, gate {rms_gate}"
 
 
 def assert_f32_close(got, ref, what: str):

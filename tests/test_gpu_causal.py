@@ -47,6 +47,10 @@ def test_f32_debug_path_block_causal(D, pairs, C, S, Fc, bf):
     (128, (22, 21, 21), 16, 20, 1, 2, 4, 1, 3, 1),  # 320-token frames: several query tiles per frame
     (128, (0, 0, 0), 2, 3, 1, 1, 5, 0, 5, 1),       # 6-token frames: many blocks inside one wave
     (128, (22, 21, 21), 6, 7, 1, 2, 6, 0, 5, 3),    # blocks of 3 in a chunk of 5: short last block
+    # 288-token frames on an empty ring: the forward is split in two key ranges, and for the queries of
+    # frame 0 that share a workgroup with queries of frame 1 the second range holds only keys they do not see
+    (128, (22, 21, 21), 16, 18, 1, 2, 3, 0, 3, 1),
+    (64, (12, 10, 10), 16, 18, 1, 1, 4, 1, 3, 1),
 ])
 def test_bf16_block_causal_streaming_fwd_bwd(D, pairs, gh, gw, B, H, C, S, Fc, bf):
     w = wl.Workload("bf16_causal", 22, B, H, D, gh, gw, C, S, Fc, 0, pairs)
@@ -134,4 +138,39 @@ def test_bf16_production_shape_frame_causal_sampled_pairs():
         assert_bf16_close(host_f64(dk[b, :, h]), rk[b, :, h], f"stream {b} head {h} dk", rep)
         assert_bf16_close(host_f64(dv[b, :, h]), rv[b, :, h], f"stream {b} head {h} dv", rep)
     _report(rep)
+    ls.close()
+
+
+def test_bf16_production_fwd_batch1_frame_causal_with_key_split():
+    """One stream of 12 heads, 18 cached frames + 3-frame chunk, frame-by-frame causality: 444
+    workgroups, so the launch is split over the keys (4 ranges) and merged; ranges of chunk keys a
+    query does not see weigh 0 in the merge.  Every head on a sample of rows around the frame and
+    tile boundaries, three heads in full; outputs pre-filled with NaN."""
+    import torch
+    w = wl.PROD_FWD
+    ls = Lockstep(w, max_chunk=3, start_frames=[7], block_frames=1)
+    pk, pv = wl.history_frame_pool(w, 6)
+    _fill_history(ls, w, pk, pv, 18)
+    q, k, v = wl.chunk_inputs(w)
+    out = torch.full((w.batch, w.n_q, w.heads, w.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.full((w.batch, w.heads, w.n_q), float("nan"), dtype=torch.float32, device="cuda:0")
+    ls.A.astro_chunk_attn_fwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), 3, out, lse)
+    torch.cuda.synchronize()
+    go, gl = host_f64(out), host_f64(lse)
+    assert np.isfinite(go).all() and np.isfinite(gl).all()
+    qf, kf, vf = (wl.bf16_bits_to_f32(x) for x in (q, k, v))
+    T = w.tokens_per_frame
+    rng = np.random.Generator(np.random.Philox(key=[w.seed, 99]))
+    edges = [0, 1, 127, 128, T - 1, T, T + 1, 2 * T - 1, 2 * T, 1535, 1536, 1663, 1664, 3 * T - 1]
+    rep = []
+    for h in range(w.heads):
+        rows = np.unique(np.concatenate([edges, rng.integers(0, w.n_q, 100)]))
+        ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, heads=[h], rows=rows)
+        assert_bf16_close(go[0, rows, h], ro[0, rows, h], f"head {h} out (row sample)", rep)
+        assert_bf16_close(gl[0, h, rows], rl[0, h, rows], f"head {h} lse (row sample)", rep)
+    for h in (0, 6, 11):
+        ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 3, heads=[h])
+        assert_bf16_close(go[0, :, h], ro[0, :, h], f"head {h} out", rep)
+        assert_bf16_close(gl[0, h], rl[0, h], f"head {h} lse", rep)
+    _report(rep[-2:])
     ls.close()

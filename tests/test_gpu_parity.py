@@ -143,9 +143,10 @@ def test_bf16_all_logits_strongly_negative_with_ragged_key_tiles():
     softmax itself is ordinary; 45-token frames leave partly filled key tiles at the end of
     the ring rows and of the chunk, whose padding must get probability exactly 0 (not
     exp(0 - LSE) times a zero row).  Keys of mean -4 make dQ = dS K a cancellation of the
-    bf16-rounded dS against that mean, and inputs of magnitude 4 instead of 1 scale the rounding
-    of dS into dK = dS^T Q: the inputs are outside the N(0,1) contract, so the gradients are gated
-    by the rounding model on the same inputs (out and LSE keep the contract)."""
+    bf16-rounded dS against that mean, inputs of magnitude 4 instead of 1 scale the rounding of dS
+    into dK = dS^T Q, and the one bf16 rounding of the staged queries (times log2(e)/sqrt(D)) moves
+    a logit of -128 by up to 0.1: the inputs are outside the N(0,1) contract, so every result is
+    gated by the rounding model on the same inputs."""
     from bf16_model import model_fwd_bwd
     w = wl.Workload("bf16_neg", 14, 1, 2, 64, 5, 9, 3, 0, 1, 0, (0, 0, 0))
     ls = Lockstep(w)
@@ -159,12 +160,12 @@ def test_bf16_all_logits_strongly_negative_with_ragged_key_tiles():
         out, lse = ls.fwd(q, k, v, 1)
         ro, rl = ls.oracle.attn_fwd(ls.wide(q), ls.wide(k), ls.wide(v), 1)
         assert rl.max() < -100.0
-        assert_bf16_close(host_f64(out), ro, f"step {step} out", rep)
-        assert_bf16_close(host_f64(lse), rl, f"step {step} lse", rep)
         dq, dk, dv = ls.A.astro_chunk_attn_bwd(ls.cache, ls.dev(q), ls.dev(k), ls.dev(v), out, lse, ls.dev(do), 1)
         rq, rk, rv = ls.oracle.attn_bwd(ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), 1)
         for h in range(w.heads):
             m = model_fwd_bwd(ls.oracle, ls.wide(q), ls.wide(k), ls.wide(v), ls.wide(do), 1, 0, h)
+            assert_within_model(host_f64(out)[0, :, h], ro[0, :, h], m[0], f"step {step} head {h} out", rep)
+            assert_within_model(host_f64(lse)[0, h], rl[0, h], m[1], f"step {step} head {h} lse", rep)
             for got, ref, mod, name in ((dq, rq, m[2], "dq"), (dk, rk, m[3], "dk"), (dv, rv, m[4], "dv")):
                 assert_within_model(host_f64(got)[0, :, h], ref[0, :, h], mod, f"step {step} head {h} {name}", rep)
         ls.append(k, v, 1)
