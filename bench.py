@@ -64,6 +64,9 @@ def main() -> int:
                     help="time the oracle on the WHOLE step (every stream and head) instead of the bounded sample")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-calibration", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for counter runs (rocprofv3 --pmc): one calibration copy of 1 GiB, then three forwards over 8 "
+                         "independent caches, then three forwards of 8 candidates over ONE shared cache, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (streams and heads shard "
@@ -96,6 +99,25 @@ def main() -> int:
             idx = torch.tensor([wl.pool_index(b, n, 4) for b in range(w.batch)], device=dev)
             A.astro_kvcache_append(cache, dk.index_select(0, idx).contiguous(), dv.index_select(0, idx).contiguous(), 1)
         return cache
+
+    if args.traffic_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        A.astro_calib_copy(src, dst)
+        del src, dst
+        for name, G in (("group_fwd_append", 1), ("shared_prefix", 8)):
+            we = wl.WORKLOADS[name]
+            ce = make_cache(we)
+            qe, ke, ve = (dev_bf16(x) for x in (wl.chunk_inputs(we) if G == 1 else wl.group_inputs(we, G)))
+            oe = torch.empty_like(qe)
+            le = torch.empty((we.batch * G, we.heads, we.n_q), dtype=torch.float32, device=dev)
+            wse = torch.empty(A.astro_group_attn_workspace_bytes(ce, we.chunk_frames, G)[0], dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                A.astro_group_attn_fwd(ce, qe, ke, ve, we.chunk_frames, G, oe, le, wse)
+            torch.cuda.synchronize()
+            ce.close()
+        print(json.dumps({"traffic_probe": "calib_copy x1, attn_fwd x3 over 8 independent caches, attn_fwd x3 of 8 candidates over one cache"}))
+        return 0
 
     # ---- main workload: fwd + bwd + append ---------------------------------------
     # The handle may reuse what a forward staged when the backward that follows it gets the same
