@@ -201,7 +201,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B{w.batch} H{w.heads} D{w.head_dim} T{w.tokens_per_frame} "
                                f"ring {w.capacity_frames} frames full, chunk {w.chunk_frames} frames "
-                               f"(Nq={w.n_q}, Nk={w.n_k}); step = attn fwd + bwd (cache detached) + KV append",
+                               f"(Nq={w.n_q}, Nk={w.n_k}); step = attn fwd + bwd (cache detached; it reuses the rotated Q / K_chunk "
+                               f"its forward staged, ASTRO_FLAG_REUSE_STAGED) + KV append; {n_sets} input sets in rotation",
                    "flops_per_step": step_flops, "frac_bf16_mfma_peak": round(value / PEAK_BF16_MFMA_TFLOPS, 4)},
         "roofline": roofline,
         "kernels": kernels,

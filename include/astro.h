@@ -178,7 +178,9 @@ int astro_chunk_attn_fwd(astro_kvcache_t *cache, const void *q, const void *k_ch
  * handle's previous attention call, with no reset or append in between, skips the rotation
  * pre-pass and reads the rotated copies that call left at the start of the workspace.  The
  * caller promises that q, k_chunk and the workspace were not written in between (by anything
- * but this library's attention calls on this handle). */
+ * but this library's attention calls on this handle).  The decision is taken on the host when
+ * the call is made: a call recorded into a HIP graph skips (or runs) the pre-pass on every
+ * replay as it did at capture, so capture the forward together with the backward that reuses it. */
 int astro_chunk_attn_bwd(astro_kvcache_t *cache, const void *q, const void *k_chunk,
                          const void *v_chunk, const void *out, const float *lse,
                          const void *dout, int32_t n_frames, float *dq, float *dk_chunk,
