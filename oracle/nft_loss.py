@@ -6,7 +6,7 @@ applied only to the masked, high-uncertainty samples; total L = L_policy + lambd
 in the form Alg. 1, Phase 2 states them.  Written as the formulas, one numpy expression
 per line; no blocking, no fusion.
 
-Readings where the paper leaves a choice (all listed in the design notes):
+Readings where the paper leaves a choice:
 * ||.||^2 is the sum of squares over ONE sample's elements; the mini-batch is averaged
   over its samples (the paper writes the loss for one sample);
 * clip(.) carries no bounds in the paper: [-1, 1] is taken, which is what makes

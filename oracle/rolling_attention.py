@@ -19,7 +19,7 @@ of every stream and masks out the frames the ring would have evicted; no ring,
 no tiling, no online softmax.  numpy matmul serves as the contraction step.
 
 The paper gives no attention formula, rotary embedding, chunk size or
-eviction order; the readings taken (all listed in the design notes) are:
+eviction order; the readings taken are:
 scaled dot-product softmax with 1/sqrt(D); every chunk query sees every chunk
 key (or, with `block_frames`, the chunk keys of its own and earlier blocks of
 that many frames: the block-causal mask at a finer block size, down to the
@@ -56,7 +56,7 @@ import numpy as np
 
 
 # ----------------------------------------------------------------------------
-# rotary embedding (reading 8/9 of the design notes)
+# rotary embedding
 # ----------------------------------------------------------------------------
 
 def rope_angles(frame: int, grid_h: int, grid_w: int, pairs: Sequence[int], base: float) -> np.ndarray:

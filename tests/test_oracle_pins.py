@@ -6,7 +6,7 @@ differences.  CPU only.
 The paper prints no worked numeric example for this path (it has no attention
 formula at all), so there is no paper-value fixture; the definitions pinned
 are those of Sec. 3.2 (sinks + rolling window), Sec. 3.3 (detached history)
-and the readings listed in the design notes.
+and the readings stated in the oracle's module docstring.
 """
 import cmath
 import math

@@ -76,7 +76,7 @@ def default_rope_pairs(head_dim: int) -> Tuple[int, int, int]:
     return (head_dim // 2 - 2 * s, s, s)
 
 
-# The five named configurations (see the workload table in the design notes).
+# The five named configurations.
 TINY_FWD = Workload("tiny_fwd", 1, 1, 2, 64, 8, 8, 4, 0, 1, 4, (12, 10, 10))
 PROD_FWD = Workload("prod_fwd", 2, 1, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21))
 GROUP_FWD_APPEND = Workload("group_fwd_append", 3, 8, 12, 128, 30, 52, 18, 0, 3, 18, (22, 21, 21))
