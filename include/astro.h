@@ -249,7 +249,8 @@ int astro_nft_loss(const void *v_theta, const void *v_old, const void *v_ref, co
  * arguments, results and errors as astro_nft_loss without the workspace: r~, the masked count and
  * the per-block partial sums live in a static device array of astro_nft_loss_static_bytes() bytes
  * (1 MiB) that every GPU the library runs on holds until the process ends.  The call allocates and
- * frees nothing and calls no allocating routine.  A size whose workspace
+ * frees nothing and calls no allocating routine (its launches are never timed by astro_profile_*,
+ * which would create events).  A size whose workspace
  * (astro_nft_loss_workspace_bytes) exceeds the array is rejected with ASTRO_ERR_WORKSPACE and
  * nothing is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on
  * one GPU (different streams or host threads) race; calls on one stream are ordered and safe, and

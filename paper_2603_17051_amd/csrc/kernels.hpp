@@ -13,7 +13,7 @@ namespace astro {
 // Times the launches made during its lifetime when profiling is on (astro_profile_begin).
 class ProfileScope {
  public:
-  ProfileScope(const char* name, hipStream_t stream);
+  ProfileScope(const char* name, hipStream_t stream, bool enabled = true);
   ~ProfileScope();
   ProfileScope(const ProfileScope&) = delete;
   ProfileScope& operator=(const ProfileScope&) = delete;

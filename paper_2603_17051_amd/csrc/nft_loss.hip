@@ -199,7 +199,7 @@ int workspace_bytes_of(int32_t n_samples, int64_t elems_per_sample, size_t* byte
 int run_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, const void* target, const float* advantage,
                  const int32_t* kl_mask, int32_t n_samples, int64_t elems_per_sample, int32_t dtype, float a_max,
                  float beta, float lambda_kl, float* loss, float* grad_v_theta, void* workspace, size_t workspace_bytes,
-                 hipStream_t stream) {
+                 hipStream_t stream, bool timed) {
   size_t need = 0;
   if (workspace_bytes_of(n_samples, elems_per_sample, &need) != ASTRO_OK) return ASTRO_ERR_INVALID_ARG;
   if (!v_theta || !v_old || !v_ref || !target || !advantage || !kl_mask || !loss || !grad_v_theta) return ASTRO_ERR_INVALID_ARG;
@@ -225,7 +225,8 @@ int run_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, cons
   p.E = elems_per_sample;
   p.inv_a_max = 1.f / a_max; p.beta = beta; p.lambda_kl = lambda_kl;
   {
-    ProfileScope prof("nft_loss", stream);
+    // the entry point that must not allocate never creates timing events, even while profiling is on
+    ProfileScope prof("nft_loss", stream, timed);
     const dim3 grid(p.blocks_per_sample, n_samples);
     if (n_samples <= kMaxSamplesInline) {
       if (dtype == ASTRO_BF16)
@@ -288,7 +289,7 @@ int astro_nft_loss(const void* v_theta, const void* v_old, const void* v_ref, co
                    float beta, float lambda_kl, float* loss, float* grad_v_theta, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
   return run_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, n_samples, elems_per_sample, dtype, a_max, beta,
-                      lambda_kl, loss, grad_v_theta, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+                      lambda_kl, loss, grad_v_theta, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream), true);
 }
 
 int astro_nft_loss_static_bytes(size_t* bytes) {
@@ -308,7 +309,7 @@ int astro_nft_loss_static(const void* v_theta, const void* v_old, const void* v_
   const int rc = static_scratch_of_current_device(&ws);
   if (rc != ASTRO_OK) return rc;
   return run_nft_loss(v_theta, v_old, v_ref, target, advantage, kl_mask, n_samples, elems_per_sample, dtype, a_max, beta,
-                      lambda_kl, loss, grad_v_theta, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream));
+                      lambda_kl, loss, grad_v_theta, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream), false);
 }
 
 }  // extern "C"

@@ -20,8 +20,8 @@ std::vector<Record> g_records;
 constexpr size_t kMaxRecords = 1 << 16;
 }  // namespace
 
-ProfileScope::ProfileScope(const char* name, hipStream_t stream) : stream_(stream), index_(-1) {
-  if (!g_on || g_records.size() >= kMaxRecords) return;
+ProfileScope::ProfileScope(const char* name, hipStream_t stream, bool enabled) : stream_(stream), index_(-1) {
+  if (!enabled || !g_on || g_records.size() >= kMaxRecords) return;
   Record r{name, nullptr, nullptr};
   if (hipEventCreate(&r.start) != hipSuccess) return;
   if (hipEventCreate(&r.stop) != hipSuccess) {
