@@ -166,7 +166,7 @@ struct DqWave {
 #pragma unroll
       for (int i = 0; i < 4 * KS; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // two vector-ALU instructions
+        __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);  // one exponential
       }
       __builtin_amdgcn_sched_barrier(0);
       ds_operand(s, dp, dsb);
