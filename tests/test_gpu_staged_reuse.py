@@ -82,3 +82,52 @@ def test_backward_reuses_what_the_forward_staged_only_when_the_call_matches():
     torch.cuda.synchronize()
     on.close()
     off.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_reuse_with_candidate_groups_and_on_the_fp32_path(dtype):
+    """The same promise for the group calls (3 candidates per stream) and for the fp32 debug path:
+    a handle with the flag gives bit-identical results to one without, with one pre-pass per
+    forward + backward instead of two."""
+    import torch
+    import paper_2603_17051_amd as A
+    w = wl.Workload("reuse_group", 18, 2, 2, 64, 4, 6, 3, 1, 2, 0, (12, 10, 10))
+    G, Fc = 3, w.chunk_frames
+    adt = A.ASTRO_BF16 if dtype == "bf16" else A.ASTRO_F32
+
+    def make(reuse):
+        c = A.astro_kvcache_create(w.batch, w.heads, w.head_dim, w.grid_h, w.grid_w, w.capacity_frames, w.sink_frames,
+                                   Fc, w.rope_pairs, w.rope_base, adt, reuse_staged=reuse)
+        shape = (w.batch, w.tokens_per_frame, w.heads, w.head_dim)
+        for n in range(2):
+            kk, vv = (wl.normal_f32(w.seed, t, shape, n) for t in (wl.T_HIST_K, wl.T_HIST_V))
+            if dtype == "bf16":
+                kk, vv = dev_bf16(wl.f32_to_bf16_bits(kk)), dev_bf16(wl.f32_to_bf16_bits(vv))
+            else:
+                kk, vv = torch.from_numpy(kk).to("cuda:0"), torch.from_numpy(vv).to("cuda:0")
+            A.astro_kvcache_append(c, kk, vv, 1)
+        return c
+
+    shape = (w.batch * G, w.n_q, w.heads, w.head_dim)
+    raw = [wl.normal_f32(w.seed, t, shape, 7) for t in (wl.T_Q, wl.T_K, wl.T_V, wl.T_DO)]
+    if dtype == "bf16":
+        q, k, v, do = (dev_bf16(wl.f32_to_bf16_bits(x)) for x in raw)
+    else:
+        q, k, v, do = (torch.from_numpy(x).to("cuda:0") for x in raw)
+    results, launches = [], []
+    for reuse in (False, True):
+        c = make(reuse)
+        ws = torch.empty(max(A.astro_group_attn_workspace_bytes(c, Fc, G)), dtype=torch.uint8, device="cuda:0")
+
+        def fwd_bwd():
+            out, lse = A.astro_group_attn_fwd(c, q, k, v, Fc, G, workspace=ws)
+            return (out, lse) + A.astro_group_attn_bwd(c, q, k, v, out, lse, do, Fc, G, workspace=ws)
+
+        res, n = _stage_launches(A, fwd_bwd)
+        torch.cuda.synchronize()
+        results.append(res)
+        launches.append(n)
+        c.close()
+    assert launches == [2, 1]
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
