@@ -23,6 +23,8 @@
 // only raised when a tile's probabilities relative to it sum to more than kSumLimit; fp32
 // accumulators and the bf16 exponent range make any smaller excess exact enough, and
 // both the row maximum and the 64 accumulator multiplies of a rescale leave the common path.
+// A query's first reference is snapped to 0 when its first tile's maximum is moderate, and a wave
+// whose references are all 0 takes exp2 of the score itself: no subtraction per score either.
 // The softmax's vector-ALU work of a tile has no independent MFMAs of the same wave to sit between
 // (taking the probabilities of the first 16 keys between the MFMAs of the other 16 was measured
 // slower as the scheduler ordered it, 3.34 vs 3.22 ms, and equal with the exact order pinned in
@@ -69,11 +71,14 @@ struct FwdWave {
   bf16x8 qreg[2][KS];
   f32x4 o[DT][2];
   float mc[2], l_run[2];  // softmax reference in log2 units (the units of the scores), per-lane partial row sum
+  // every reference of the wave is exactly 0 (wave-uniform): the exponent is the score itself
+  bool zero_ref;
   OperandAddr16<D> addr;
   int g;
 
   __device__ __forceinline__ void init(int lane) {
     g = lane >> 4;
+    zero_ref = false;
     addr.init(lane);
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
@@ -86,9 +91,10 @@ struct FwdWave {
       for (int qs = 0; qs < 2; ++qs) o[dt][qs] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // p = exp2(s - mc) rounded to bf16, packed as the B operands of the PV
+  // p = exp2(s - mc) (kZeroRef: mc is 0 for the whole wave, no subtraction) rounded to bf16, packed as the B operands of the PV
   // product (k-slots 8g .. 8g+3 <- keys 4g .., 8g+4 .. <- keys 16 + 4g ..); sum = this lane's
   // part of the row sums, taken over the rounded values.
+  template <bool kZeroRef>
   __device__ __forceinline__ void probabilities(const f32x4 (&s)[2][2], bf16x8 (&pb)[2], float (&sum)[2]) const {
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
@@ -97,7 +103,8 @@ struct FwdWave {
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
         for (int r = 0; r < 4; r += 2) {
-          const f32x2 e = {fast_exp2(s[kh][qs][r] - mc[qs]), fast_exp2(s[kh][qs][r + 1] - mc[qs])};
+          const f32x2 e = kZeroRef ? f32x2{fast_exp2(s[kh][qs][r]), fast_exp2(s[kh][qs][r + 1])}
+                                   : f32x2{fast_exp2(s[kh][qs][r] - mc[qs]), fast_exp2(s[kh][qs][r + 1] - mc[qs])};
           const bf16x2 pk = __builtin_convertvector(e, bf16x2);
           sum[qs] = add_pair(pk, sum[qs]);
           pb[qs][4 * kh + r] = pk[0];
@@ -177,7 +184,10 @@ struct FwdWave {
     {
       f32x4 s[2][2];
       scores<kTail>(kf, ks, live, any_dead, s);
-      probabilities(s, pb, sum);
+      if (__builtin_expect(zero_ref, 1))
+        probabilities<true>(s, pb, sum);
+      else
+        probabilities<false>(s, pb, sum);
     }
     if (__builtin_expect(__any(!(sum[0] <= kSumLimit) || !(sum[1] <= kSumLimit)), 0)) {
       f32x4 s[2][2];
@@ -190,7 +200,12 @@ struct FwdWave {
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         // never below -1e28: a query that has seen nothing but masked keys so far (scores of
         // -1e30) keeps probabilities of exactly 0 instead of exp2(rounding error of 1e29)
-        const float mc_new = fmaxf(fmaxf(mc[qs], mx), -1.0e28f);
+        float mc_new = fmaxf(fmaxf(mc[qs], mx), -1.0e28f);
+        // A query's FIRST reference (nothing accumulated yet) is snapped to 0 when its tile maximum
+        // is moderate, as it is for any ordinary logits: while every reference of the wave is 0 the
+        // common path needs no subtraction in front of the exponential.  fp32 sums and the bf16
+        // exponent range hold 2^44 above and 2^-90 below such a reference.
+        if (mc[qs] < -1.0e27f && mc_new > -32.f && mc_new < 32.f) mc_new = 0.f;
         const float alpha = fast_exp2(mc[qs] - mc_new);
         l_run[qs] *= alpha;
         // whole-tuple products: the compiler then updates the accumulators where they are
@@ -199,7 +214,8 @@ struct FwdWave {
         for (int dt = 0; dt < DT; ++dt) o[dt][qs] = o[dt][qs] * alpha;
         mc[qs] = mc_new;
       }
-      probabilities(s, pb, sum);
+      zero_ref = __all(mc[0] == 0.f && mc[1] == 0.f);
+      probabilities<false>(s, pb, sum);
     }
     l_run[0] += sum[0];
     l_run[1] += sum[1];
