@@ -1,7 +1,8 @@
 """GPU parity over WHOLE tensors at the production shapes: every (stream, head) pair of the
 backward shape (batch 4, 12 heads: the contiguous per-XCD work mapping), every head of the
 batch-1 forward (key split active), every pair of the 8-stream forward on a row sample plus one
-full pair per stream.  Outputs are pre-filled with NaN, so a pair or row that no workgroup wrote
+full pair per stream; and every pair of a 16-pair D = 64 case with ragged frames, a sink and a
+wrapped ring.  Outputs are pre-filled with NaN, so a pair or row that no workgroup wrote
 fails the finiteness check before any comparison."""
 import numpy as np
 import pytest
@@ -133,4 +134,39 @@ def test_bf16_grouped_streams_fwd_every_pair():
         assert_bf16_close(go[b, :, h], ro[b, :, h], f"stream {b} head {h} out (full)", rep)
         assert_bf16_close(gl[b, h], rl[b, h], f"stream {b} head {h} lse (full)", rep)
         print(f"    stream {b} ok: {rep[-2]}", flush=True)
+    ls.close()
+
+
+def test_bf16_head_dim_64_every_pair_after_eviction():
+    """D = 64 kernels with 16 (stream, head) pairs (the per-XCD mapping), 130-token frames (ragged
+    tiles everywhere), one sink frame and a ring that has wrapped: out, LSE, dQ, dK, dV of every
+    pair in full."""
+    import torch
+    w = wl.Workload("d64_every_pair", 31, 2, 8, 64, 10, 13, 6, 1, 2, 0, (12, 10, 10))
+    ls = Lockstep(w, max_chunk=2, start_frames=[3, 40])
+    _fill_history(ls, w, 5, 9)  # 9 frames into a ring of 6: three evictions behind the sink
+    ls.check_tables()
+    q, k, v, do = wl.chunk_inputs(w, with_dout=True)
+    dq_, dk_, dv_ = (_nan_like((w.batch, w.n_q, w.heads, w.head_dim), torch.float32) for _ in range(3))
+    out = _nan_like((w.batch, w.n_q, w.heads, w.head_dim), torch.bfloat16)
+    lse = _nan_like((w.batch, w.heads, w.n_q), torch.float32)
+    q_d, k_d, v_d, do_d = ls.dev(q), ls.dev(k), ls.dev(v), ls.dev(do)
+    ls.A.astro_chunk_attn_fwd(ls.cache, q_d, k_d, v_d, 2, out, lse)
+    ls.A.astro_chunk_attn_bwd(ls.cache, q_d, k_d, v_d, out, lse, do_d, 2, dq_, dk_, dv_)
+    torch.cuda.synchronize()
+    got = {n: host_f64(t) for n, t in (("out", out), ("lse", lse), ("dq", dq_), ("dk", dk_), ("dv", dv_))}
+    for n, a in got.items():
+        assert np.isfinite(a).all(), f"{n}: elements no workgroup wrote"
+    qf, kf, vf, dof = (wl.bf16_bits_to_f32(x) for x in (q, k, v, do))
+    ro, rl = ls.oracle.attn_fwd(qf, kf, vf, 2)
+    rq, rk, rv = ls.oracle.attn_bwd(qf, kf, vf, dof, 2)
+    rep = []
+    for b in range(w.batch):
+        for h in range(w.heads):
+            assert_bf16_close(got["out"][b, :, h], ro[b, :, h], f"stream {b} head {h} out", rep)
+            assert_bf16_close(got["lse"][b, h], rl[b, h], f"stream {b} head {h} lse", rep)
+            assert_bf16_close(got["dq"][b, :, h], rq[b, :, h], f"stream {b} head {h} dq", rep)
+            assert_bf16_close(got["dk"][b, :, h], rk[b, :, h], f"stream {b} head {h} dk", rep)
+            assert_bf16_close(got["dv"][b, :, h], rv[b, :, h], f"stream {b} head {h} dv", rep)
+    print("   ", rep[-5], flush=True)
     ls.close()
